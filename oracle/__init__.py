@@ -1,0 +1,5 @@
+"""Float64 CPU oracle of the OBRS hot path -- test infrastructure only.
+
+Nothing in the product package imports this; only ``tests/``, the smoke check
+and the benchmark's ``cpu_baseline`` leg do.
+"""

@@ -1,0 +1,312 @@
+/*
+ * OBRS oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, float64 CPU statement of what the Jackpot / OBRS hot path
+ * computes, written from the paper's definitions.  Only the test-suite, the
+ * smoke check and the benchmark's cpu_baseline leg may call it.  It shares no
+ * code, header, table or helper with the HIP library and neither side
+ * includes the other.
+ *
+ * Notation (paper Sec. 3.1 / Sec. 4.1): q = softmax(actor logits) is the
+ * rollout ("inference") distribution p_inf, p = softmax(policy logits) is the
+ * target distribution p_target, lambda > 0 the rejection threshold, x the
+ * token that was sampled from q.
+ *
+ * Every function below is pinned by tests that do not call it to produce
+ * their expected value (closed forms, brute force on tiny vocabularies,
+ * library routines, theorems of Sec. 3.3 / App. A).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { JPO_F32 = 0, JPO_BF16 = 1, JPO_F64 = 2 };
+
+/* Per-row results.  Field order is mirrored by the ctypes binding. */
+typedef struct {
+    double lse_q, lse_p;        /* log-sum-exp of the two logit rows            */
+    double logq_x, logp_x;      /* log q(x), log p(x) of the sampled token      */
+    double logratio;            /* log p(x) - log q(x)                          */
+    double accept;              /* a(x) = min(1, p(x) / (lambda q(x)))          */
+    double z_approx;            /* sum over V_k of min(q, p/lambda)             */
+    double z_exact;             /* sum over the vocabulary of min(q, p/lambda)  */
+    double kl_p_q;              /* KL(p || q)                                   */
+    double kl_p_qtilde;         /* KL(p || q~), q~ = min(q, p/lambda)/Z         */
+    int32_t mask;               /* 1 iff u < a(x)                               */
+    int32_t union_size;         /* |V_k|                                        */
+    int32_t valid;              /* 0 for a padding row (x < 0)                  */
+    int32_t pad_;
+} jpo_row_out;
+
+/* Batch results (Sec. 4.4.2). */
+typedef struct {
+    int64_t n_valid;            /* proposed tokens B                            */
+    int64_t n_accept;           /* accepted tokens                              */
+    double alpha_hat;           /* n_accept / n_valid                           */
+    double mean_z_approx;       /* (1/B) sum_i Z_approx^(i)                     */
+    double kappa;               /* alpha_hat / mean_z_approx                    */
+    double mean_z_exact;
+    double mean_accept;         /* (1/B) sum_i a(x_i)                           */
+} jpo_batch_out;
+
+/* ---- exact widening of stored logits ---------------------------------- */
+
+static double bf16_to_double(uint16_t h)
+{
+    /* bfloat16 is the upper half of an IEEE binary32. */
+    uint32_t w = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+void jpo_widen_row(const void *src, int dtype, int64_t V, double *dst)
+{
+    if (dtype == JPO_F32) {
+        const float *s = (const float *)src;
+        for (int64_t v = 0; v < V; ++v) dst[v] = (double)s[v];
+    } else if (dtype == JPO_BF16) {
+        const uint16_t *s = (const uint16_t *)src;
+        for (int64_t v = 0; v < V; ++v) dst[v] = bf16_to_double(s[v]);
+    } else {
+        memcpy(dst, src, (size_t)V * sizeof(double));
+    }
+}
+
+/* ---- softmax in the log domain ----------------------------------------
+ * The distribution of a language model is the softmax of its logits
+ * (Sec. 2).  log softmax(l)_v = l_v - LSE(l),
+ * LSE(l) = m + log sum_v exp(l_v - m), m = max_v l_v.               */
+double jpo_logsumexp(const double *l, int64_t V)
+{
+    double m = -INFINITY;
+    for (int64_t v = 0; v < V; ++v)
+        if (l[v] > m) m = l[v];
+    if (!(m > -INFINITY)) return m;          /* all -inf (or empty) */
+    double s = 0.0;
+    for (int64_t v = 0; v < V; ++v) s += exp(l[v] - m);
+    return m + log(s);
+}
+
+/* ---- top-k(p): the k most probable tokens (Sec. 4.4.1) ----------------
+ * Selection is on the logits (softmax is monotone).  Equal values are
+ * ordered by the lowest token id first.  The whole id list is sorted and
+ * the first k entries are returned, in that order.                    */
+static const double *g_sort_key;
+#ifdef _OPENMP
+#pragma omp threadprivate(g_sort_key)
+#endif
+
+static int cmp_desc_value_asc_id(const void *a, const void *b)
+{
+    int32_t ia = *(const int32_t *)a, ib = *(const int32_t *)b;
+    double va = g_sort_key[ia], vb = g_sort_key[ib];
+    if (va > vb) return -1;
+    if (va < vb) return 1;
+    return (ia > ib) - (ia < ib);
+}
+
+void jpo_topk(const double *l, int64_t V, int32_t k, int32_t *ids_out)
+{
+    int32_t *ids = (int32_t *)malloc((size_t)V * sizeof(int32_t));
+    for (int64_t v = 0; v < V; ++v) ids[v] = (int32_t)v;
+    g_sort_key = l;
+    qsort(ids, (size_t)V, sizeof(int32_t), cmp_desc_value_asc_id);
+    for (int32_t j = 0; j < k; ++j) ids_out[j] = ids[j];
+    free(ids);
+}
+
+/* min(q_v, p_v / lambda): the un-normalised post-rejection mass of token v
+ * (Eq. obrs_dist; App. A.1). */
+static double kept_mass(double logq_v, double logp_v, double lambda)
+{
+    double qv = exp(logq_v);
+    double pv = exp(logp_v) / lambda;
+    return qv < pv ? qv : pv;
+}
+
+/* ---- one token position ------------------------------------------------
+ * lq, lp: logits of the rollout and the target model over V tokens.
+ * x: sampled token (x < 0 marks a padding row), u: uniform in [0,1).
+ * topk_q / topk_p (each k ids) may be NULL.                              */
+void jpo_row(const double *lq, const double *lp, int64_t V, int32_t x, double u,
+             double lambda, int32_t k, jpo_row_out *out, int32_t *topk_q, int32_t *topk_p)
+{
+    memset(out, 0, sizeof *out);
+    if (x < 0) return;
+    out->valid = 1;
+
+    double lse_q = jpo_logsumexp(lq, V);
+    double lse_p = jpo_logsumexp(lp, V);
+    out->lse_q = lse_q;
+    out->lse_p = lse_p;
+
+    /* log-probabilities of the sampled token and their difference */
+    out->logq_x = lq[x] - lse_q;
+    out->logp_x = lp[x] - lse_p;
+    out->logratio = out->logp_x - out->logq_x;
+
+    /* Eq. obrs_accept: a(x) = min(1, p(x) / (lambda q(x))) */
+    double r = exp(out->logratio) / lambda;
+    out->accept = r < 1.0 ? r : 1.0;
+
+    /* Mask(x) ~ Bernoulli(a(x)), realised as U(0,1) < a  (Alg. 2) */
+    out->mask = (u < out->accept) ? 1 : 0;
+
+    /* V_k = top-k(q) U top-k(p), a set (Sec. 4.4.1) */
+    int32_t *kq = (int32_t *)malloc((size_t)k * sizeof(int32_t));
+    int32_t *kp = (int32_t *)malloc((size_t)k * sizeof(int32_t));
+    jpo_topk(lq, V, k, kq);
+    jpo_topk(lp, V, k, kp);
+    unsigned char *in_union = (unsigned char *)calloc((size_t)V, 1);
+    for (int32_t j = 0; j < k; ++j) in_union[kq[j]] = 1;
+    for (int32_t j = 0; j < k; ++j) in_union[kp[j]] = 1;
+
+    /* Z_approx over V_k, Z over the whole vocabulary, both in id order */
+    double z_approx = 0.0, z_exact = 0.0;
+    int32_t usize = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        double t = kept_mass(lq[v] - lse_q, lp[v] - lse_p, lambda);
+        z_exact += t;
+        if (in_union[v]) {
+            z_approx += t;
+            ++usize;
+        }
+    }
+    out->z_approx = z_approx;
+    out->z_exact = z_exact;
+    out->union_size = usize;
+
+    /* diagnostics used only by the oracle's own pins: KL(p||q), KL(p||q~) */
+    double kl_pq = 0.0, kl_pqt = 0.0;
+    for (int64_t v = 0; v < V; ++v) {
+        double logp_v = lp[v] - lse_p, logq_v = lq[v] - lse_q;
+        double pv = exp(logp_v);
+        if (pv > 0.0) {
+            double qt = kept_mass(logq_v, logp_v, lambda) / z_exact;
+            kl_pq += pv * (logp_v - logq_v);
+            kl_pqt += pv * (logp_v - log(qt));
+        }
+    }
+    out->kl_p_q = kl_pq;
+    out->kl_p_qtilde = kl_pqt;
+
+    if (topk_q) memcpy(topk_q, kq, (size_t)k * sizeof(int32_t));
+    if (topk_p) memcpy(topk_p, kp, (size_t)k * sizeof(int32_t));
+    free(in_union);
+    free(kp);
+    free(kq);
+}
+
+/* Post-rejection distribution q~_v = min(q_v, p_v/lambda) / Z for one row
+ * (Eq. obrs_dist), written to qt[V]; returns Z. */
+double jpo_post_rejection(const double *lq, const double *lp, int64_t V, double lambda, double *qt)
+{
+    double lse_q = jpo_logsumexp(lq, V), lse_p = jpo_logsumexp(lp, V);
+    double z = 0.0;
+    for (int64_t v = 0; v < V; ++v) {
+        qt[v] = kept_mass(lq[v] - lse_q, lp[v] - lse_p, lambda);
+        z += qt[v];
+    }
+    for (int64_t v = 0; v < V; ++v) qt[v] /= z;
+    return z;
+}
+
+/* ---- a batch of rows stored in their input dtype -----------------------
+ * actor / policy: [T, V] row-major with row_stride elements between rows.
+ * Rows are independent, so they may be computed by several threads; each
+ * row is computed exactly as jpo_row does.  Returns the threads used.   */
+int jpo_rows(const void *actor, const void *policy, int dtype, int64_t T, int64_t V,
+             int64_t row_stride, const int32_t *x, const float *u, double lambda, int32_t k,
+             jpo_row_out *out, int32_t *topk_q, int32_t *topk_p, int n_threads)
+{
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+#else
+    {
+#endif
+        double *lq = (double *)malloc((size_t)V * sizeof(double));
+        double *lp = (double *)malloc((size_t)V * sizeof(double));
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t t = 0; t < T; ++t) {
+            const char *ra = (const char *)actor + (size_t)t * (size_t)row_stride * esz;
+            const char *rp = (const char *)policy + (size_t)t * (size_t)row_stride * esz;
+            jpo_widen_row(ra, dtype, V, lq);
+            jpo_widen_row(rp, dtype, V, lp);
+            jpo_row(lq, lp, V, x[t], u ? (double)u[t] : 2.0, lambda, k, &out[t],
+                    topk_q ? topk_q + (size_t)t * k : NULL, topk_p ? topk_p + (size_t)t * k : NULL);
+        }
+        free(lp);
+        free(lq);
+    }
+    return used;
+}
+
+/* ---- batch-level bias correction and weights (Sec. 4.4.2, Alg. 1 step 2-3)
+ * mask[t] is taken as given (the Bernoulli draw is an input of this stage).
+ * alpha_hat = accepted / proposed;  kappa = alpha_hat / mean(Z_approx);
+ * Z_t = kappa Z_approx;  w = Z_t max(lambda, p(x)/q(x));
+ * rho = min(w, c1) * min(p_ref(x)/p(x), c2)   (second factor 1 if no ref).
+ * use_expected_alpha != 0 replaces alpha_hat by the mean of a(x).        */
+void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double lambda,
+               double c1, double c2, const double *ref_logprob, int use_expected_alpha,
+               jpo_batch_out *b, double *w_out, double *rho_out)
+{
+    memset(b, 0, sizeof *b);
+    double sz = 0.0, sze = 0.0, sa = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        if (!rows[t].valid) continue;
+        b->n_valid += 1;
+        b->n_accept += mask[t] ? 1 : 0;
+        sz += rows[t].z_approx;
+        sze += rows[t].z_exact;
+        sa += rows[t].accept;
+    }
+    double n = (double)b->n_valid;
+    b->alpha_hat = (double)b->n_accept / n;
+    b->mean_z_approx = sz / n;
+    b->mean_z_exact = sze / n;
+    b->mean_accept = sa / n;
+    double alpha = use_expected_alpha ? b->mean_accept : b->alpha_hat;
+    b->kappa = alpha / b->mean_z_approx;
+
+    for (int64_t t = 0; t < T; ++t) {
+        if (!rows[t].valid) {
+            if (w_out) w_out[t] = 0.0;
+            if (rho_out) rho_out[t] = 0.0;
+            continue;
+        }
+        double z_t = b->kappa * rows[t].z_approx;
+        double ratio = exp(rows[t].logratio);
+        double w = z_t * (lambda > ratio ? lambda : ratio);
+        double rho = w < c1 ? w : c1;
+        if (ref_logprob) {
+            double rr = exp(ref_logprob[t] - rows[t].logp_x);
+            rho *= rr < c2 ? rr : c2;
+        }
+        if (w_out) w_out[t] = w;
+        if (rho_out) rho_out[t] = rho;
+    }
+}
+
+int jpo_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,407 @@
+"""Pins for the float64 oracle: what the paper and the mathematics fix, computed here without
+calling the oracle for the expected value (closed forms, brute force, library routines,
+theorems).  A plausible slip anywhere in the oracle (dropped term, swapped p/q, wrong sign,
+wrong tie-break, union counted twice) fails at least one of these.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import obrs_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _softmax64(l):
+    l = np.asarray(l, dtype=np.float64)
+    return scipy.special.softmax(l)
+
+
+def _rand_logits(rng, V, sigma=2.0):
+    return rng.normal(0.0, sigma, V)
+
+
+def _rows_from(outs):
+    arr = np.zeros(len(outs), dtype=orc.ROW_DTYPE)
+    for i, o in enumerate(outs):
+        for name in orc.ROW_DTYPE.names:
+            arr[name][i] = getattr(o, name)
+    return arr
+
+
+# ---- P10: a worked two-token example (derived by hand from Eq. obrs_accept / obrs_dist and
+# the weight of Alg. 1 step 3; values stored in tests/golden/two_token_example.txt) -------------
+
+def _read_golden(name):
+    vals = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            k, v = line.split("=")
+            vals[k.strip()] = [float(t) for t in v.split(",")]
+    return vals
+
+
+def test_two_token_hand_example():
+    g = _read_golden("two_token_example.txt")
+    q, p, lam = np.array(g["q"]), np.array(g["p"]), g["lambda"][0]
+    lq, lp = np.log(q), np.log(p) + 3.25          # logits are defined up to a shift
+    for x in (0, 1):
+        out, kq, kp = orc.row(lq, lp, x, 0.0, lam, 2)
+        assert out.accept == pytest.approx(g["accept"][x], rel=1e-14)
+        assert out.z_exact == pytest.approx(g["Z"][0], rel=1e-14)
+        assert out.z_approx == pytest.approx(g["Z"][0], rel=1e-14)
+        assert out.logratio == pytest.approx(math.log(p[x] / q[x]), abs=1e-14)
+        b, w, rho = orc.batch(_rows_from([out]), [1], lam, 1e9, 1e9)
+        # kappa rescales Z; the un-corrected weight is w / kappa = Z * max(lambda, p/q)
+        assert w[0] / b.kappa == pytest.approx(g["w"][x], rel=1e-13)
+    qt, z = orc.post_rejection(lq, lp, lam)
+    np.testing.assert_allclose(qt, g["q_tilde"], rtol=1e-14)
+    assert list(kq) == [0, 1]          # q ties -> lowest id first
+    assert list(kp) == [0, 1]
+
+
+# ---- P12: log-sum-exp / log-softmax against library routines --------------------------------
+
+@pytest.mark.parametrize("V,sigma", [(1, 1.0), (7, 3.0), (1024, 2.0), (5000, 30.0)])
+def test_logsumexp_matches_scipy(V, sigma):
+    rng = np.random.default_rng(V)
+    l = _rand_logits(rng, V, sigma)
+    assert orc.logsumexp(l) == pytest.approx(scipy.special.logsumexp(l), rel=1e-14, abs=1e-14)
+    out, _, _ = orc.row(l, l + 1.0, V // 2, 0.5, 1.0, 1)
+    assert out.logq_x == pytest.approx(scipy.special.log_softmax(l)[V // 2], abs=1e-12)
+
+
+def test_logsumexp_large_offset_and_minus_inf():
+    l = np.array([1000.0, 1000.0, -np.inf, 999.0])
+    assert orc.logsumexp(l) == pytest.approx(1000.0 + math.log(2.0 + math.exp(-1.0)), rel=1e-15)
+    l = np.array([-1000.0, -1001.0])
+    assert orc.logsumexp(l) == pytest.approx(-1000.0 + math.log1p(math.exp(-1.0)), rel=1e-15)
+
+
+# ---- top-k: order (value desc, id asc) against a stable library sort and an O(V^2) rank count --
+
+@pytest.mark.parametrize("V,k", [(16, 5), (300, 300), (1024, 32), (4096, 256)])
+def test_topk_matches_stable_argsort(V, k):
+    rng = np.random.default_rng(V + k)
+    l = np.round(rng.normal(0, 1, V) * 4) / 4          # coarse grid -> many exact ties
+    want = np.argsort(-l, kind="stable")[:k]
+    np.testing.assert_array_equal(orc.topk(l, k), want)
+
+
+def test_topk_rank_count_bruteforce():
+    rng = np.random.default_rng(5)
+    for V in (3, 8, 16):
+        l = rng.integers(-2, 3, V).astype(np.float64)
+        for k in range(1, V + 1):
+            got = orc.topk(l, k)
+            rank = [sum((l[j] > l[i]) or (l[j] == l[i] and j < i) for j in range(V)) for i in range(V)]
+            want = sorted(range(V), key=lambda i: rank[i])[:k]
+            assert list(got) == want
+
+
+# ---- P11: constant rows pin tie-break and the set union ---------------------------------------
+
+@pytest.mark.parametrize("lam", [0.5, 1.0, 4.0])
+def test_constant_logits(lam):
+    V, k = 96, 10
+    out, kq, kp = orc.row(np.full(V, 1.5), np.full(V, -0.25), 17, 0.3, lam, k)
+    assert list(kq) == list(range(k)) and list(kp) == list(range(k))
+    assert out.union_size == k
+    assert out.z_exact == pytest.approx(min(1.0, 1.0 / lam), rel=1e-13)
+    assert out.z_approx == pytest.approx(k / V * min(1.0, 1.0 / lam), rel=1e-13)
+
+
+def test_union_is_a_set_and_bounds():
+    # q peaks on ids 0..3, p on ids 2..5 -> union of top-4 lists has 6 members
+    lq = np.array([9., 8., 7., 6., 0., 0., 0., 0.])
+    lp = np.array([0., 0., 7., 9., 8., 6., 0., 0.])
+    out, kq, kp = orc.row(lq, lp, 0, 0.5, 1.0, 4)
+    assert list(kq) == [0, 1, 2, 3] and list(kp) == [3, 4, 2, 5]
+    assert out.union_size == 6
+    q, p = _softmax64(lq), _softmax64(lp)
+    assert out.z_approx == pytest.approx(np.minimum(q, p)[:6].sum(), rel=1e-13)
+
+
+# ---- P1, P2, P7: normaliser identities --------------------------------------------------------
+
+@pytest.mark.parametrize("lam", [0.3, 1.0, 2.5])
+def test_normaliser_identities(lam):
+    rng = np.random.default_rng(11)
+    V = 257
+    lq, lp = _rand_logits(rng, V), _rand_logits(rng, V)
+    q, p = _softmax64(lq), _softmax64(lp)
+    qt, z = orc.post_rejection(lq, lp, lam)
+    assert qt.sum() == pytest.approx(1.0, abs=1e-13)                       # P1
+    a = np.minimum(1.0, p / (lam * q))
+    assert z == pytest.approx((q * a).sum(), rel=1e-13)                    # P2: Z = E_q[a]
+    A = p / q > lam                                                        # P7: partition form
+    assert z == pytest.approx(q[A].sum() + p[~A].sum() / lam, rel=1e-13)
+    assert z <= min(1.0, 1.0 / lam) + 1e-15
+    out, _, _ = orc.row(lq, lp, 3, 0.5, lam, 8)
+    assert out.z_exact == pytest.approx(z, rel=1e-14)
+    assert out.accept == pytest.approx(a[3], rel=1e-13)
+
+
+# ---- P3: matched distributions ------------------------------------------------------------------
+
+@pytest.mark.parametrize("lam", [0.25, 1.0, 3.0])
+def test_matched_distributions(lam):
+    rng = np.random.default_rng(3)
+    V = 200
+    l = _rand_logits(rng, V)
+    for x in (0, 57, V - 1):
+        out, _, _ = orc.row(l, l - 7.0, x, 0.999, lam, V)      # a shift of the logits changes nothing
+        assert out.logratio == pytest.approx(0.0, abs=1e-13)
+        assert out.accept == pytest.approx(min(1.0, 1.0 / lam), rel=1e-13)
+        assert out.z_exact == pytest.approx(min(1.0, 1.0 / lam), rel=1e-13)
+        b, w, _ = orc.batch(_rows_from([out]), [1], lam, 1e9, 1e9)
+        assert w[0] / b.kappa == pytest.approx(1.0, rel=1e-12)     # p / q~ = 1
+
+
+# ---- strict "<" of the Bernoulli draw (Alg. 2) ----------------------------------------------
+
+def test_mask_is_strict_less_than():
+    l = np.array([0.0, 1.0, 2.0])
+    out, _, _ = orc.row(l, l, 1, 0.5, 2.0, 1)           # a = 1/2 exactly
+    assert out.accept == 0.5 and out.mask == 0
+    out, _, _ = orc.row(l, l, 1, np.nextafter(0.5, 0.0), 2.0, 1)
+    assert out.mask == 1
+    out, _, _ = orc.row(l, l, 1, 0.0, 1.0, 1)
+    assert out.mask == 1
+
+
+# ---- P4, P5: the top-k estimate --------------------------------------------------------------
+
+def test_topk_estimate_monotone_and_exact_at_full_k():
+    rng = np.random.default_rng(21)
+    V = 512
+    lq = _rand_logits(rng, V, 3.0)
+    lp = lq + rng.normal(0, 1.5, V)
+    prev = 0.0
+    for k in (1, 2, 5, 20, 100, 400, V):
+        out, _, _ = orc.row(lq, lp, 0, 0.5, 1.3, k)
+        assert out.z_approx <= out.z_exact + 1e-15
+        assert out.z_approx >= prev - 1e-15
+        assert k <= out.union_size <= min(2 * k, V)
+        prev = out.z_approx
+    assert out.z_approx == out.z_exact                  # k = V: identical sums, bit for bit
+    assert out.union_size == V
+
+
+def test_topk_estimate_against_numpy():
+    rng = np.random.default_rng(22)
+    V, k, lam = 1000, 20, 0.8
+    lq = _rand_logits(rng, V, 3.0)
+    lp = lq + rng.normal(0, 2.0, V)
+    q, p = _softmax64(lq), _softmax64(lp)
+    U = set(np.argsort(-lq, kind="stable")[:k]) | set(np.argsort(-lp, kind="stable")[:k])
+    want = sum(min(q[v], p[v] / lam) for v in sorted(U))
+    out, _, _ = orc.row(lq, lp, 5, 0.5, lam, k)
+    assert out.union_size == len(U)
+    assert out.z_approx == pytest.approx(want, rel=1e-12)
+
+
+# ---- P6: Sec. 3.3 theorem, App. A proposition and corollary ------------------------------------
+
+def _kl(p, r):
+    m = p > 0
+    return float((p[m] * (np.log(p[m]) - np.log(r[m]))).sum())
+
+
+def test_kl_contraction_and_monotonicity():
+    rng = np.random.default_rng(31)
+    for V in (5, 64, 700):
+        lq, lp = _rand_logits(rng, V), _rand_logits(rng, V)
+        q, p = _softmax64(lq), _softmax64(lp)
+        ratio = p / q
+        kl_pq = _kl(p, q)
+        prev = None
+        for lam in (ratio.min() * 0.5, 0.2, 0.7, 1.0, 1.9, 6.0, ratio.max() * 1.01):
+            out, _, _ = orc.row(lq, lp, 0, 0.5, lam, 1)
+            assert out.kl_p_q == pytest.approx(kl_pq, rel=1e-11, abs=1e-13)
+            qt, _ = orc.post_rejection(lq, lp, lam)
+            assert out.kl_p_qtilde == pytest.approx(_kl(p, qt), rel=1e-9, abs=1e-12)
+            assert out.kl_p_qtilde <= kl_pq + 1e-12
+        for lam in sorted([ratio.min() * 0.5, 0.2, 0.7, 1.0, 1.9, 6.0, ratio.max() * 1.01]):
+            out, _, _ = orc.row(lq, lp, 0, 0.5, lam, 1)
+            if prev is not None:
+                assert out.kl_p_qtilde <= prev + 1e-12      # non-increasing in lambda
+            prev = out.kl_p_qtilde
+        qt, z = orc.post_rejection(lq, lp, ratio.max() * 1.01)   # classical rejection sampling
+        np.testing.assert_allclose(qt, p, rtol=1e-12)
+        assert z == pytest.approx(1.0 / (ratio.max() * 1.01), rel=1e-12)
+        qt, z = orc.post_rejection(lq, lp, ratio.min() * 0.5)    # everything accepted
+        np.testing.assert_allclose(qt, q, rtol=1e-12)
+        assert z == pytest.approx(1.0, rel=1e-12)
+
+
+# ---- P8: w = p / q~ -------------------------------------------------------------------------
+
+def test_weight_is_ratio_to_post_rejection_distribution():
+    rng = np.random.default_rng(41)
+    V, lam = 50, 1.2
+    lq, lp = _rand_logits(rng, V), _rand_logits(rng, V)
+    p = _softmax64(lp)
+    qt, _ = orc.post_rejection(lq, lp, lam)
+    for x in range(0, V, 7):
+        out, _, _ = orc.row(lq, lp, x, 0.5, lam, V)
+        b, w, _ = orc.batch(_rows_from([out]), [1], lam, 1e9, 1e9)
+        assert (w[0] / b.kappa) * qt[x] == pytest.approx(p[x], rel=1e-12)
+
+
+# ---- P9: exhaustive brute force on tiny vocabularies ---------------------------------------------
+
+def test_bruteforce_tiny_vocab():
+    rng = np.random.default_rng(51)
+    for V in (2, 3, 5, 9, 16):
+        for lam in (0.5, 1.0, 2.0):
+            lq = np.round(rng.normal(0, 1.5, V) * 2) / 2
+            lp = np.round(rng.normal(0, 1.5, V) * 2) / 2
+            eq, ep = np.exp(lq), np.exp(lp)
+            q, p = eq / eq.sum(), ep / ep.sum()
+            kept = np.array([q[x] * min(1.0, p[x] / (lam * q[x])) for x in range(V)])
+            Z = kept.sum()
+            for k in (1, max(1, V // 2), V):
+                def rank(l, i):
+                    return sum((l[j] > l[i]) or (l[j] == l[i] and j < i) for j in range(V))
+                bits = 0
+                for i in range(V):
+                    if rank(lq, i) < k:
+                        bits |= 1 << i
+                    if rank(lp, i) < k:
+                        bits |= 1 << i
+                members = [i for i in range(V) if bits >> i & 1]
+                for x in range(V):
+                    out, kq, kp = orc.row(lq, lp, x, 0.5, lam, k)
+                    assert out.accept * q[x] == pytest.approx(kept[x], rel=1e-12)   # P(x kept)
+                    assert out.z_exact == pytest.approx(Z, rel=1e-12)
+                    assert out.union_size == len(members)
+                    assert sorted(set(kq) | set(kp)) == members
+                    assert out.z_approx == pytest.approx(kept[members].sum(), rel=1e-12)
+
+
+def test_budget_optimality_against_random_rules():
+    # App. A.2: among acceptance rules with the same budget sum_v q_v alpha_v = Z, none gives a
+    # smaller KL(p || kept) than the OBRS rule.
+    rng = np.random.default_rng(61)
+    V, lam = 8, 0.9
+    lq, lp = _rand_logits(rng, V, 1.0), _rand_logits(rng, V, 1.0)
+    q, p = _softmax64(lq), _softmax64(lp)
+    out, _, _ = orc.row(lq, lp, 0, 0.5, lam, 1)
+    a_star = np.minimum(1.0, p / (lam * q))
+    budget = (q * a_star).sum()
+    for _ in range(300):
+        a = a_star.copy()
+        for _ in range(6):                       # budget-preserving pairwise moves inside [0,1]^V
+            i, j = rng.choice(V, 2, replace=False)
+            hi = min((1 - a[i]) * q[i], a[j] * q[j])
+            d = rng.uniform(0, hi) * 0.9
+            a[i] += d / q[i]
+            a[j] -= d / q[j]
+        assert (q * a).sum() == pytest.approx(budget, rel=1e-12)
+        kept = q * a / budget
+        assert _kl(p, kept) >= out.kl_p_qtilde - 1e-12
+
+
+# ---- P12b: Monte-Carlo run of the sampling loop of Alg. 2 ---------------------------------------
+
+def test_monte_carlo_sampler_matches_post_rejection_distribution():
+    rng = np.random.default_rng(71)
+    V, lam, N = 6, 1.4, 400_000
+    lq, lp = _rand_logits(rng, V, 1.0), _rand_logits(rng, V, 1.0)
+    q, p = _softmax64(lq), _softmax64(lp)
+    xs = rng.choice(V, size=N, p=q)
+    us = rng.random(N)
+    acc = us < np.minimum(1.0, p[xs] / (lam * q[xs]))
+    qt, z = orc.post_rejection(lq, lp, lam)
+    rate = acc.mean()
+    assert abs(rate - z) < 4 * math.sqrt(z * (1 - z) / N)
+    hist = np.bincount(xs[acc], minlength=V) / acc.sum()
+    assert np.all(np.abs(hist - qt) < 4 * np.sqrt(qt * (1 - qt) / acc.sum()) + 1e-9)
+
+
+# ---- batch stage: bias correction (Sec. 4.4.2) -------------------------------------------------
+
+def test_kappa_closed_forms_and_padding():
+    l = np.array([0.0, 1.0, 2.0, 3.0])
+    outs = [orc.row(l, l, t % 4, 0.5, 1.0, 1)[0] for t in range(8)]     # Z_approx = q(3) each
+    outs.append(orc.row(l, l, -1, 0.5, 1.0, 1)[0])                       # padding row
+    rows = _rows_from(outs)
+    q3 = float(_softmax64(l)[3])
+    mask = [1, 1, 1, 0, 1, 1, 0, 1, 1]                                   # 6 of 8 valid accepted
+    b, w, rho = orc.batch(rows, mask, 1.0, 0.7, 1e9)
+    assert (b.n_valid, b.n_accept) == (8, 6)
+    assert b.alpha_hat == pytest.approx(0.75)
+    assert b.mean_z_approx == pytest.approx(q3, rel=1e-14)
+    assert b.kappa == pytest.approx(0.75 / q3, rel=1e-14)
+    np.testing.assert_allclose(w[:8], 0.75, rtol=1e-13)                  # kappa Z max(1, 1) = alpha
+    np.testing.assert_allclose(rho[:8], 0.7, rtol=1e-13)                 # clipped by c1
+    assert w[8] == 0.0 and rho[8] == 0.0
+    b2, _, _ = orc.batch(rows, mask, 1.0, 0.7, 1e9, use_expected_alpha=True)
+    assert b2.kappa == pytest.approx(1.0 / q3, rel=1e-14)                # mean a = 1
+
+
+def test_rho_reference_factor():
+    rng = np.random.default_rng(81)
+    lq, lp = _rand_logits(rng, 30), _rand_logits(rng, 30)
+    out, _, _ = orc.row(lq, lp, 4, 0.1, 1.0, 30)
+    rows = _rows_from([out])
+    _, w, rho0 = orc.batch(rows, [1], 1.0, 1e9, 3.0)
+    for fac, c2, want in ((2.0, 3.0, 2.0), (5.0, 3.0, 3.0), (0.25, 3.0, 0.25)):
+        ref = np.array([out.logp_x + math.log(fac)])
+        _, w2, rho = orc.batch(rows, [1], 1.0, 1e9, c2, ref_logprob=ref)
+        assert w2[0] == w[0]
+        assert rho[0] == pytest.approx(rho0[0] * want, rel=1e-13)
+
+
+def test_bias_correction_recovers_true_normaliser():
+    # Z equals the expected acceptance rate, so kappa * Z_approx estimates Z without bias:
+    # many draws x ~ q at one position, Bernoulli(a(x)) masks, small k.
+    rng = np.random.default_rng(91)
+    V, lam, k, B = 40, 1.0, 2, 60_000
+    lq = _rand_logits(rng, V, 1.0)
+    lp = lq + rng.normal(0, 1.0, V)
+    q = _softmax64(lq)
+    per_x = [orc.row(lq, lp, x, 0.0, lam, k)[0] for x in range(V)]
+    xs = rng.choice(V, size=B, p=q)
+    us = rng.random(B)
+    rows = _rows_from([per_x[x] for x in xs])
+    mask = (us < rows["accept"]).astype(np.int32)
+    b, _, _ = orc.batch(rows, mask, lam, 1e9, 1e9)
+    z = per_x[0].z_exact
+    assert per_x[0].z_approx < 0.9 * z                       # the raw estimate is biased low
+    assert abs(b.kappa * per_x[0].z_approx - z) < 4 * math.sqrt(z * (1 - z) / B)
+
+
+# ---- multi-row driver equals the single-row routine, for every storage dtype ---------------------
+
+def test_rows_driver_matches_single_rows_and_widens_exactly():
+    rng = np.random.default_rng(101)
+    T, V, k = 9, 333, 7
+    a32 = rng.normal(0, 2, (T, V)).astype(np.float32)
+    p32 = (a32 + rng.normal(0, 1, (T, V))).astype(np.float32)
+    x = rng.integers(0, V, T).astype(np.int32)
+    x[4] = -1
+    u = rng.random(T).astype(np.float32)
+    bits_a = (a32.view(np.uint32) >> 16).astype(np.uint16)        # truncation: any bf16 pattern will do
+    bits_p = (p32.view(np.uint32) >> 16).astype(np.uint16)
+    for A, P in ((a32, p32), (bits_a, bits_p)):
+        if A.dtype == np.uint16:
+            A64 = (A.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+            P64 = (P.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        else:
+            A64, P64 = A.astype(np.float64), P.astype(np.float64)
+        R = orc.rows(A, P, x, u, 1.1, k, n_threads=3)
+        for t in range(T):
+            out, kq, kp = orc.row(A64[t], P64[t], x[t], float(u[t]), 1.1, k)
+            for name in ("logq_x", "logp_x", "accept", "z_approx", "z_exact", "mask", "valid"):
+                assert R.out[name][t] == getattr(out, name)
+            if x[t] >= 0:
+                np.testing.assert_array_equal(R.topk_q[t], kq)
+                np.testing.assert_array_equal(R.topk_p[t], kp)
