@@ -1,0 +1,151 @@
+/*
+ * jp_obrs.h -- C ABI of the MI355X (gfx950) OBRS hot path of Jackpot.
+ *
+ * Per token position t, from the rollout-model ("actor", p_inf, written q) logits and the
+ * target-model ("policy", p_target, written p) logits over the whole vocabulary:
+ *
+ *   a_t        = min(1, p(x_t) / (lambda q(x_t)))                     Sec. 4.1, Eq. obrs_accept
+ *   mask_t     = (u_t < a_t)                                          Sec. 4.2 (1); App. A Alg. 2
+ *   V_k        = top-k(q) U top-k(p)  (a set)                         Sec. 4.4.1
+ *   Z_approx,t = sum_{v in V_k} min(q(v), p(v)/lambda)                Sec. 4.4.1; Alg. 1 step 2
+ *   Z_t (diagnostic) = sum_{v in V} min(q(v), p(v)/lambda)            Sec. 4.1, Eq. obrs_dist
+ *   alpha_hat  = accepted / proposed,  kappa = alpha_hat / mean_t Z_approx,t      Sec. 4.4.2
+ *   w_t        = kappa Z_approx,t max(lambda, p(x_t)/q(x_t))          Alg. 1 step 3
+ *   rho_t      = min(w_t, c1) min(p_ref(x_t)/p(x_t), c2)              Alg. 1 step 3
+ *
+ * Conventions
+ *   - Every pointer argument is a DEVICE pointer unless it is a params / outputs struct
+ *     (those are host structs read during the call).  The caller owns all buffers for the
+ *     lifetime of the enqueued work.  Inputs are never written.
+ *   - The library allocates nothing and never synchronises: all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream).
+ *   - Logit tensors are [T, V] row-major with `row_stride` ELEMENTS between consecutive rows
+ *     (row_stride >= V).  Base pointers must be 16-byte aligned and row_stride * sizeof(element)
+ *     must be a multiple of 16.
+ *   - top-k lists are ordered by (logit descending, token id ascending); ties therefore go to
+ *     the lowest id.
+ *   - A row with sampled_ids[t] < 0 is padding: it is skipped, its outputs are 0 (top-k ids
+ *     -1) and it is not counted in the batch statistics.
+ *   - Errors the host can see return a status before anything is launched.  Errors only the
+ *     device can see (sampled id >= V, non-finite log-sum-exp, no valid row) set bits in
+ *     jp_obrs_stats.error_flags and put NaN in the affected outputs.
+ *   - Re-entrant; no global state.  Calls that share a workspace must be ordered by the caller.
+ */
+#ifndef JP_OBRS_H
+#define JP_OBRS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define JP_K_MAX 256            /* largest supported top-k count per distribution */
+
+typedef enum jp_status {
+    JP_OK = 0,
+    JP_ERR_NULL = 1,            /* a required pointer is NULL                          */
+    JP_ERR_SHAPE = 2,           /* T < 0, V <= 0, row_stride < V, sizes out of range   */
+    JP_ERR_PARAM = 3,           /* lambda / c1 / c2 not positive or NaN, k < 1, k > V  */
+    JP_ERR_ALIGN = 4,           /* pointer or row pitch not 16-byte aligned            */
+    JP_ERR_WORKSPACE = 5,       /* workspace NULL or smaller than jp_obrs_workspace_bytes */
+    JP_ERR_UNSUPPORTED = 6,     /* k > JP_K_MAX, unknown dtype or flag                 */
+    JP_ERR_HIP = 7              /* a HIP launch failed                                 */
+} jp_status;
+
+typedef enum jp_dtype { JP_F32 = 0, JP_BF16 = 1 } jp_dtype;
+
+enum {
+    JP_FLAG_EXACT_Z = 1,        /* also compute Z over the whole vocabulary (second sweep)  */
+    JP_FLAG_TOPK_LOGPROBS = 2,  /* also write log-probabilities of the two top-k lists      */
+    JP_FLAG_ALPHA_EXPECTED = 4  /* alpha_hat := mean_t a_t instead of accepted/proposed     */
+};
+
+enum {                          /* bits of jp_obrs_stats.error_flags */
+    JP_DATA_ERR_ID_RANGE = 1,   /* some sampled id >= V                      */
+    JP_DATA_ERR_NONFINITE = 2,  /* some row had a NaN / +inf log-sum-exp     */
+    JP_DATA_ERR_EMPTY = 4       /* no valid row: kappa is NaN                */
+};
+
+typedef struct jp_obrs_params {
+    float lambda;               /* rejection threshold, > 0 (paper default 1.0)            */
+    int32_t k;                  /* top-k count per distribution, 1 <= k <= min(V, JP_K_MAX) */
+    float c1;                   /* clip of w_OBRS, > 0 (+inf disables)                     */
+    float c2;                   /* clip of p_ref/p, > 0 (+inf disables)                    */
+    uint32_t flags;             /* JP_FLAG_*                                               */
+} jp_obrs_params;
+
+/* Batch statistics, written to device memory by the finalize stage (Sec. 4.4.2). */
+typedef struct jp_obrs_stats {
+    int64_t n_valid;            /* proposed tokens B (non-padding, error-free rows) */
+    int64_t n_accept;           /* sum_t mask_t                                     */
+    double alpha_hat;           /* n_accept / n_valid (or mean a_t, see flags)      */
+    double mean_z_approx;       /* (1/B) sum_t Z_approx,t                           */
+    double kappa;               /* alpha_hat / mean_z_approx                        */
+    double mean_z_exact;        /* (1/B) sum_t Z_t, NaN without JP_FLAG_EXACT_Z     */
+    double mean_accept;         /* (1/B) sum_t a_t                                  */
+    uint32_t error_flags;       /* JP_DATA_ERR_*                                    */
+    uint32_t reserved;
+} jp_obrs_stats;
+
+/* Output pointers (device memory, caller-owned).  NULL = not wanted. */
+typedef struct jp_obrs_outputs {
+    float *accept_prob;         /* [T]   a_t                                               */
+    uint8_t *mask;              /* [T]   1 = accepted (needs uniforms)                     */
+    float *logq;                /* [T]   log q(x_t)                                        */
+    float *logp;                /* [T]   log p(x_t)                                        */
+    float *logratio;            /* [T]   log p(x_t) - log q(x_t)                           */
+    float *z_approx;            /* [T]                                                     */
+    float *z_exact;             /* [T]   required with JP_FLAG_EXACT_Z                     */
+    float *w_obrs;              /* [T]   un-clipped w_t (not multiplied by the mask)       */
+    float *rho;                 /* [T]   rho_t          (not multiplied by the mask)       */
+    int32_t *union_size;        /* [T]   |V_k|                                             */
+    int32_t *topk_actor;        /* [T,k] ids of top-k(q)                                   */
+    int32_t *topk_policy;       /* [T,k] ids of top-k(p)                                   */
+    float *topk_actor_logq;     /* [T,k] log q of topk_actor,  with JP_FLAG_TOPK_LOGPROBS  */
+    float *topk_policy_logp;    /* [T,k] log p of topk_policy, with JP_FLAG_TOPK_LOGPROBS  */
+    jp_obrs_stats *stats;       /* one struct, written by the finalize stage               */
+} jp_obrs_outputs;
+
+/* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */
+size_t jp_obrs_workspace_bytes(int64_t T, int64_t V, int32_t k, jp_dtype dt, uint32_t flags);
+
+/*
+ * The whole hot path: row stage (log-sum-exp of both rows, sampled-token log-probs, both top-k
+ * lists, a_t, mask_t, Z_approx,t [, Z_t]) followed by the batch stage (alpha_hat, kappa, w_t,
+ * rho_t).  uniforms == NULL implies JP_FLAG_ALPHA_EXPECTED and no mask; ref_logprob == NULL
+ * makes the p_ref/p factor 1.  T == 0 is valid and does nothing but write the stats.
+ */
+jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits,
+                          int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                          const int32_t *sampled_ids,   /* [T] x_t                       */
+                          const float *uniforms,        /* [T] u_t in [0,1), or NULL     */
+                          const float *ref_logprob,     /* [T] log p_ref(x_t), or NULL   */
+                          const jp_obrs_params *prm, const jp_obrs_outputs *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Row stage only (everything of jp_obrs_forward that needs no batch statistic). */
+jp_status jp_obrs_rows(const void *actor_logits, const void *policy_logits,
+                       int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                       const int32_t *sampled_ids, const float *uniforms,
+                       const jp_obrs_params *prm, const jp_obrs_outputs *out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Batch stage only (Sec. 4.4.2 and Alg. 1 step 3) over the per-row results that a preceding
+ * jp_obrs_rows call with the SAME workspace, T and outputs struct left behind.
+ */
+jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *ref_logprob,
+                           const jp_obrs_params *prm, const jp_obrs_outputs *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+const char *jp_status_string(jp_status s);
+
+/* ABI version of this header (bumped on incompatible change). */
+int jp_obrs_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JP_OBRS_H */

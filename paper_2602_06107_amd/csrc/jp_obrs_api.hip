@@ -1,0 +1,203 @@
+// C-ABI entry points: argument validation, workspace carving, launches.  No allocation, no sync.
+#include <math.h>
+#include <stdint.h>
+
+#include "jp_obrs_internal.h"
+
+namespace {
+
+constexpr uint32_t KNOWN_FLAGS = JP_FLAG_EXACT_Z | JP_FLAG_TOPK_LOGPROBS | JP_FLAG_ALPHA_EXPECTED;
+constexpr size_t ALIGN = 256;
+
+size_t round_up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Scratch kept between the row stage and the batch stage (user buffers replace the float
+// arrays when the caller asked for those outputs).
+struct Workspace {
+    float *accept, *logq, *logp, *logratio, *zapprox, *zexact;
+    double *lse_q, *lse_p;
+    uint8_t *mask, *rowflag;
+    jp_obrs_stats *stats;
+    size_t bytes;
+};
+
+Workspace carve(void *base, int64_t T)
+{
+    Workspace w;
+    char *p = (char *)base;
+    size_t off = 0;
+    const size_t n = (size_t)(T > 0 ? T : 0);
+    auto take = [&](size_t bytes) { char *r = p ? p + off : nullptr; off += round_up(bytes); return r; };
+    w.accept = (float *)take(n * 4);
+    w.logq = (float *)take(n * 4);
+    w.logp = (float *)take(n * 4);
+    w.logratio = (float *)take(n * 4);
+    w.zapprox = (float *)take(n * 4);
+    w.zexact = (float *)take(n * 4);
+    w.lse_q = (double *)take(n * 8);
+    w.lse_p = (double *)take(n * 8);
+    w.mask = (uint8_t *)take(n);
+    w.rowflag = (uint8_t *)take(n);
+    w.stats = (jp_obrs_stats *)take(sizeof(jp_obrs_stats));
+    w.bytes = off;
+    return w;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+jp_status check_params(const jp_obrs_params *prm, int64_t V, bool need_clips)
+{
+    if (!prm) return JP_ERR_NULL;
+    if (prm->flags & ~KNOWN_FLAGS) return JP_ERR_UNSUPPORTED;
+    if (!(prm->lambda > 0.f) || !isfinite(prm->lambda)) return JP_ERR_PARAM;
+    if (need_clips && (!(prm->c1 > 0.f) || !(prm->c2 > 0.f))) return JP_ERR_PARAM;
+    if (prm->k < 1 || (int64_t)prm->k > V) return JP_ERR_PARAM;
+    if (prm->k > JP_K_MAX) return JP_ERR_UNSUPPORTED;
+    return JP_OK;
+}
+
+jp_status check_shape(int64_t T, int64_t V, int64_t row_stride, jp_dtype dt)
+{
+    if (dt != JP_F32 && dt != JP_BF16) return JP_ERR_UNSUPPORTED;
+    if (T < 0 || T > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || row_stride < V) return JP_ERR_SHAPE;
+    return JP_OK;
+}
+
+jp_status rows_impl(const void *actor, const void *policy, int64_t T, int64_t V, int64_t row_stride,
+                    jp_dtype dt, const int32_t *ids, const float *uni, const jp_obrs_params *prm,
+                    const jp_obrs_outputs *out, void *workspace, size_t workspace_bytes,
+                    hipStream_t st, bool need_clips)
+{
+    if (!prm || !out) return JP_ERR_NULL;
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s != JP_OK) return s;
+    s = check_params(prm, V, need_clips);
+    if (s != JP_OK) return s;
+    if (T > 0 && (!actor || !policy || !ids)) return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(actor) || !aligned16(policy) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < jp_obrs_workspace_bytes(T, V, prm->k, dt, prm->flags)) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+    if (T == 0) return JP_OK;
+
+    const Workspace w = carve(workspace, T);
+    jp::RowArgs a{};
+    a.actor = actor; a.policy = policy; a.T = T; a.V = V; a.stride = row_stride;
+    a.ids = ids; a.uni = uni; a.lambda = prm->lambda; a.k = prm->k;
+    a.accept = out->accept_prob ? out->accept_prob : w.accept;
+    a.logq = out->logq ? out->logq : w.logq;
+    a.logp = out->logp ? out->logp : w.logp;
+    a.logratio = out->logratio ? out->logratio : w.logratio;
+    a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+    a.lse_q = w.lse_q; a.lse_p = w.lse_p;
+    a.mask = out->mask ? out->mask : w.mask;
+    a.rowflag = w.rowflag;
+    a.usize = out->union_size;
+    a.topk_a = out->topk_actor; a.topk_p = out->topk_policy;
+    const bool lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) != 0;
+    a.topk_a_lq = lp ? out->topk_actor_logq : nullptr;
+    a.topk_p_lp = lp ? out->topk_policy_logp : nullptr;
+    if (jp::launch_rows(a, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
+
+    if (prm->flags & JP_FLAG_EXACT_Z) {
+        jp::ZExactArgs z{};
+        z.actor = actor; z.policy = policy; z.T = T; z.V = V; z.stride = row_stride;
+        z.lse_q = w.lse_q; z.lse_p = w.lse_p; z.rowflag = w.rowflag; z.lambda = prm->lambda;
+        z.zexact = out->z_exact ? out->z_exact : w.zexact;
+        if (jp::launch_zexact(z, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
+    }
+    return JP_OK;
+}
+
+jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, const float *ref_logprob,
+                        const jp_obrs_params *prm, const jp_obrs_outputs *out, void *workspace,
+                        size_t workspace_bytes, hipStream_t st, bool have_uniforms)
+{
+    (void)ids; (void)uni_given;
+    if (!prm || !out) return JP_ERR_NULL;
+    if (T < 0 || T > 0x7fffffffLL) return JP_ERR_SHAPE;
+    if (prm->flags & ~KNOWN_FLAGS) return JP_ERR_UNSUPPORTED;
+    if (!(prm->lambda > 0.f) || !isfinite(prm->lambda) || !(prm->c1 > 0.f) || !(prm->c2 > 0.f)) return JP_ERR_PARAM;
+    const Workspace w = carve(workspace, T);
+    if (!workspace || workspace_bytes < w.bytes) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+
+    jp::FinalizeArgs f{};
+    f.T = T;
+    f.rowflag = w.rowflag;
+    f.mask = out->mask ? out->mask : w.mask;
+    f.accept = out->accept_prob ? out->accept_prob : w.accept;
+    f.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+    f.zexact = (prm->flags & JP_FLAG_EXACT_Z) ? (out->z_exact ? out->z_exact : w.zexact) : nullptr;
+    f.logratio = out->logratio ? out->logratio : w.logratio;
+    f.logp = out->logp ? out->logp : w.logp;
+    f.ref_logprob = ref_logprob;
+    f.lambda = prm->lambda; f.c1 = prm->c1; f.c2 = prm->c2;
+    f.alpha_expected = ((prm->flags & JP_FLAG_ALPHA_EXPECTED) || !have_uniforms) ? 1 : 0;
+    f.stats = out->stats ? out->stats : w.stats;
+    f.w = out->w_obrs; f.rho = out->rho;
+    if (jp::launch_finalize(f, st) != hipSuccess) return JP_ERR_HIP;
+    return JP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t jp_obrs_workspace_bytes(int64_t T, int64_t V, int32_t k, jp_dtype dt, uint32_t flags)
+{
+    (void)flags;
+    if (T < 0 || T > 0x7fffffffLL || V <= 0 || k < 1 || (dt != JP_F32 && dt != JP_BF16)) return 0;
+    return carve(nullptr, T).bytes;
+}
+
+jp_status jp_obrs_rows(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
+                       int64_t row_stride, jp_dtype dt, const int32_t *sampled_ids,
+                       const float *uniforms, const jp_obrs_params *prm, const jp_obrs_outputs *out,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    return rows_impl(actor_logits, policy_logits, T, V, row_stride, dt, sampled_ids, uniforms, prm, out,
+                     workspace, workspace_bytes, (hipStream_t)stream, false);
+}
+
+jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *ref_logprob,
+                           const jp_obrs_params *prm, const jp_obrs_outputs *out, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    // Whether uniforms were supplied is not known here: the caller states it through
+    // JP_FLAG_ALPHA_EXPECTED (set it when the row stage ran without uniforms).
+    return finalize_impl(T, sampled_ids, nullptr, ref_logprob, prm, out, workspace, workspace_bytes,
+                         (hipStream_t)stream, true);
+}
+
+jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
+                          int64_t row_stride, jp_dtype dt, const int32_t *sampled_ids,
+                          const float *uniforms, const float *ref_logprob, const jp_obrs_params *prm,
+                          const jp_obrs_outputs *out, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    jp_status s = rows_impl(actor_logits, policy_logits, T, V, row_stride, dt, sampled_ids, uniforms, prm,
+                            out, workspace, workspace_bytes, (hipStream_t)stream, true);
+    if (s != JP_OK) return s;
+    return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes,
+                         (hipStream_t)stream, uniforms != nullptr);
+}
+
+const char *jp_status_string(jp_status s)
+{
+    switch (s) {
+    case JP_OK: return "ok";
+    case JP_ERR_NULL: return "required pointer is NULL";
+    case JP_ERR_SHAPE: return "invalid shape";
+    case JP_ERR_PARAM: return "invalid parameter";
+    case JP_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
+    case JP_ERR_WORKSPACE: return "workspace missing or too small";
+    case JP_ERR_UNSUPPORTED: return "unsupported dtype, flag or k";
+    case JP_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int jp_obrs_abi_version(void) { return 1; }
+
+}  // extern "C"

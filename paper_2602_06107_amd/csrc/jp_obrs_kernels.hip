@@ -1,0 +1,681 @@
+// OBRS hot path of Jackpot for gfx950 (MI355X): device kernels.
+//
+// One 64-lane wavefront owns one token position.  It streams the actor and the policy logit
+// rows once with 16-byte loads and keeps, per row:
+//   * a running sum of 2^(l*log2(e) - M2) against a wave-uniform reference M2 (log-sum-exp),
+//   * a bounded buffer of "chunk descriptors" (chunk maximum, chunk index) in LDS from which
+//     the k chunks with the largest maxima survive (the k largest elements of a row always lie
+//     inside the k chunks with the largest maxima),
+// then expands the surviving chunks into elements, ranks them by (logit desc, id asc), forms the
+// union of the two top-k lists and the normaliser estimate of Sec. 4.4.1, and the per-token
+// acceptance probability of Eq. obrs_accept.  A second, optional sweep computes the normaliser
+// of Eq. obrs_dist over the whole vocabulary; two small kernels do the batch statistics of
+// Sec. 4.4.2 and the weights of Alg. 1 step 3.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "jp_obrs_internal.h"
+
+namespace jp {
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr float LOG2E_F = 1.4426950408889634f;
+constexpr double LOG2E_D = 1.4426950408889634074;
+constexpr double LN2_D = 0.69314718055994530942;
+// The exponent reference moves only when a logit exceeds it by this many powers of two, so a
+// row sum stays below 2^64 * V, far inside fp32 range.
+constexpr float RESCALE_MARGIN2 = 64.0f;
+constexpr float M2_UNSET = -3.0e38f;
+
+__device__ __forceinline__ float neg_inf() { return __uint_as_float(0xff800000u); }
+
+// Order-preserving map float -> uint32 (-0 is folded onto +0 so that equal values get equal keys).
+__device__ __forceinline__ uint32_t ord32(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u = (u == 0x80000000u) ? 0u : u;
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float unord32(uint32_t o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
+}
+
+__device__ __forceinline__ int lane_prefix(uint64_t m)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uniform_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+__device__ __forceinline__ uint32_t uniform_u(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
+{
+    return ((uint64_t)uniform_u((uint32_t)(v >> 32)) << 32) | uniform_u((uint32_t)v);
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// Single-wave workgroups: this orders LDS traffic between lanes (and stops the compiler from
+// moving LDS accesses across it).
+__device__ __forceinline__ void lds_sync() { __syncthreads(); }
+
+// ---- element types ------------------------------------------------------------------------
+
+struct Bf16Elem {
+    static constexpr int VEC = 8;           // elements per 16-byte load
+    static constexpr int ESZ = 2;
+    static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[VEC])
+    {
+        f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
+        f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+        f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
+        f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float load1(const char *row, int64_t i)
+    {
+        return __uint_as_float((uint32_t)((const uint16_t *)row)[i] << 16);
+    }
+};
+
+struct F32Elem {
+    static constexpr int VEC = 4;
+    static constexpr int ESZ = 4;
+    static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[VEC])
+    {
+        f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+        f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+    }
+    static __device__ __forceinline__ float load1(const char *row, int64_t i) { return ((const float *)row)[i]; }
+};
+
+// ---- chunk descriptors: (chunk maximum, chunk index) packed so that an unsigned compare orders
+// them by (maximum desc, index asc).  Valid keys are never 0. --------------------------------
+
+struct Key32 {                     // bf16 only: 16 value bits + 16 index bits
+    using Key = uint32_t;
+    static constexpr int KEYBITS = 32;
+    static constexpr int VALBITS = 16;
+    static __device__ __forceinline__ Key make(float cmax, uint32_t c) { return (ord32(cmax) & 0xffff0000u) | (0xffffu - c); }
+    static __device__ __forceinline__ uint32_t ord(Key k) { return k & 0xffff0000u; }
+    static __device__ __forceinline__ uint32_t chunk(Key k) { return 0xffffu - (k & 0xffffu); }
+    static __device__ __forceinline__ float value(Key k)
+    {
+        uint32_t o = k & 0xffff0000u;
+        return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : (~o & 0xffff0000u));
+    }
+};
+
+struct Key64 {
+    using Key = uint64_t;
+    static constexpr int KEYBITS = 64;
+    static constexpr int VALBITS = 32;
+    static __device__ __forceinline__ Key make(float cmax, uint32_t c) { return ((uint64_t)ord32(cmax) << 32) | (uint64_t)(0xffffffffu - c); }
+    static __device__ __forceinline__ uint32_t ord(Key k) { return (uint32_t)(k >> 32); }
+    static __device__ __forceinline__ uint32_t chunk(Key k) { return 0xffffffffu - (uint32_t)k; }
+    static __device__ __forceinline__ float value(Key k) { return unord32((uint32_t)(k >> 32)); }
+};
+
+template <class Key> __device__ __forceinline__ Key uniform_key(Key k);
+template <> __device__ __forceinline__ uint32_t uniform_key<uint32_t>(uint32_t k) { return uniform_u(k); }
+template <> __device__ __forceinline__ uint64_t uniform_key<uint64_t>(uint64_t k) { return uniform_u64(k); }
+
+// Threshold the streaming loop compares chunk maxima against: the value part of `k`, or -inf
+// while no threshold has been established.
+template <class KT> __device__ __forceinline__ float threshold_value(typename KT::Key k)
+{
+    float v = KT::value(k);
+    return (KT::ord(k) <= 0x007fffffu) ? neg_inf() : v;     // ord(-inf) = 0x007fffff
+}
+
+// ---- keep the k largest of cnt keys held in buf (LDS) -----------------------------------------
+// Bitwise radix select over wave ballots.  After the value bits the loop may stop early: the
+// prefix found so far is a lower bound of the k-th largest key with at least k keys above it,
+// which is all the streaming filter needs.  exact=true runs every bit, leaving exactly
+// min(cnt, k) keys.  Returns the new count; `prefix` receives the bound (0 if cnt < k).
+template <class KT, int NS>
+__device__ __forceinline__ int select_top_keys(typename KT::Key *buf, int cnt, int k, bool exact,
+                                               int early_limit, typename KT::Key &prefix_out)
+{
+    using Key = typename KT::Key;
+    const int lane = threadIdx.x;
+    lds_sync();
+    Key kk[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        int e = s * WAVE + lane;
+        kk[s] = (e < cnt) ? buf[e] : (Key)0;
+    }
+    Key prefix = 0;
+    int bit = KT::KEYBITS - 1;
+    auto step = [&](int b) {
+        Key cand = prefix | ((Key)1 << b);
+        int n = 0;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) n += __popcll(__ballot(kk[s] >= cand));
+        if (n >= k) prefix = cand;
+    };
+    for (; bit >= KT::KEYBITS - KT::VALBITS; --bit) step(bit);
+    int nge = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) nge += __popcll(__ballot(kk[s] >= prefix && kk[s] != 0));
+    if (exact || nge > early_limit) {
+        for (; bit >= 0; --bit) step(bit);
+    }
+    lds_sync();
+    int n = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        bool keep = kk[s] >= prefix && kk[s] != 0;
+        uint64_t m = __ballot(keep);
+        if (keep) buf[n + lane_prefix(m)] = kk[s];
+        n += __popcll(m);
+    }
+    lds_sync();
+    prefix_out = prefix;
+    return n;
+}
+
+// Per-row, per-tensor streaming state.  Everything except `s` is wave-uniform.
+template <class Key> struct Stream {
+    float s;          // per-lane partial sum of 2^(l*log2e - M2)
+    float M2;         // exponent reference (log2 domain)
+    float mthr;       // logits above this force M2 to move
+    float tauv;       // chunk maxima below this cannot enter the top-k
+    Key tauk;         // exact form of the same bound (keys below it are not inserted)
+    int cnt;          // descriptors currently buffered
+};
+
+template <class KT, int C, int NS>
+__device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typename KT::Key *buf,
+                                            float cmax, uint32_t c, bool pass, int k)
+{
+    using Key = typename KT::Key;
+    if (__ballot(pass) == 0) return;
+    Key key = KT::make(cmax, c);
+    bool ins = pass && key >= st.tauk;
+    uint64_t bm = __ballot(ins);
+    if (bm) {
+        if (ins) buf[st.cnt + lane_prefix(bm)] = key;
+        st.cnt += __popcll(bm);
+        if (st.cnt + WAVE > C) {
+            Key pre;
+            st.cnt = select_top_keys<KT, NS>(buf, st.cnt, k, false, C / 2, pre);
+            pre = uniform_key<Key>(pre);
+            st.tauk = pre > (Key)1 ? pre : (Key)1;
+            st.tauv = uniform_f(threshold_value<KT>(st.tauk));
+        }
+    }
+    if (__ballot(pass && cmax > st.mthr)) {
+        float wm = uniform_f(wave_max(pass ? cmax : neg_inf()));
+        float newM2 = wm * LOG2E_F;
+        st.s *= __builtin_amdgcn_exp2f(st.M2 - newM2);
+        st.M2 = newM2;
+        st.mthr = wm + RESCALE_MARGIN2 / LOG2E_F;
+    }
+}
+
+template <int VEC> __device__ __forceinline__ float max_of(const float (&f)[VEC])
+{
+    float m = f[0];
+#pragma unroll
+    for (int j = 1; j < VEC; ++j) m = fmaxf(m, f[j]);
+    return m;
+}
+
+template <int VEC> __device__ __forceinline__ float sum_exp2(const float (&f)[VEC], float M2)
+{
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; j += 2) {
+        a += __builtin_amdgcn_exp2f(__builtin_fmaf(f[j], LOG2E_F, -M2));
+        b += __builtin_amdgcn_exp2f(__builtin_fmaf(f[j + 1], LOG2E_F, -M2));
+    }
+    return a + b;
+}
+
+// Load chunk c of a row: a plain 16-byte load for full chunks, element loads (padded with -inf)
+// for the ragged tail chunk.
+template <class ET>
+__device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t nfull, int tail,
+                                           float (&f)[ET::VEC])
+{
+    if (c < nfull) {
+        uint4 w = ((const uint4 *)row)[c];
+        ET::unpack(w, f);
+    } else {
+#pragma unroll
+        for (int j = 0; j < ET::VEC; ++j)
+            f[j] = (j < tail) ? ET::load1(row, (int64_t)c * ET::VEC + j) : neg_inf();
+    }
+}
+
+}  // namespace
+
+// =================================================================================================
+// Row kernel: S1-S5 of the hot path for one token position per wavefront.
+// =================================================================================================
+template <class ET, class KT, int KC>
+__global__ __launch_bounds__(64) void row_kernel(RowArgs A)
+{
+    using Key = typename KT::Key;
+    constexpr int VEC = ET::VEC;
+    constexpr int C = 4 * KC;             // descriptor buffer capacity per tensor
+    constexpr int NS = C / WAVE;
+    constexpr int E = 2 * KC + WAVE;      // element candidate capacity
+    constexpr int ES = E / WAVE;
+
+    __shared__ Key s_desc[2][C];
+    __shared__ uint32_t s_ord[E], s_id[E], s_oth[E];
+    __shared__ uint32_t l_id[2][KC];
+    __shared__ float l_a[2][KC], l_b[2][KC];
+
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int k = A.k;
+    const int64_t V = A.V;
+    const float NaN = __uint_as_float(0x7fc00000u);
+
+    const int x = A.ids[t];
+    if (x < 0 || x >= V) {                // padding row, or a sampled id outside the vocabulary
+        const bool pad = x < 0;
+        const float fill = pad ? 0.f : NaN;
+        if (lane == 0) {
+            A.rowflag[t] = pad ? ROW_PADDING : ROW_BAD_ID;
+            A.accept[t] = fill; A.logq[t] = fill; A.logp[t] = fill; A.logratio[t] = fill;
+            A.zapprox[t] = fill; A.lse_q[t] = fill; A.lse_p[t] = fill;
+            if (A.mask) A.mask[t] = 0;
+            if (A.usize) A.usize[t] = 0;
+        }
+        for (int r = lane; r < k; r += WAVE) {
+            if (A.topk_a) A.topk_a[t * k + r] = -1;
+            if (A.topk_p) A.topk_p[t * k + r] = -1;
+            if (A.topk_a_lq) A.topk_a_lq[t * k + r] = fill;
+            if (A.topk_p_lp) A.topk_p_lp[t * k + r] = fill;
+        }
+        return;
+    }
+
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const uint4 *vq = (const uint4 *)rowq;
+    const uint4 *vp = (const uint4 *)rowp;
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
+    const uint32_t nit = nfull / WAVE;
+
+    Stream<Key> sq{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
+    Stream<Key> sp{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
+
+    auto consume = [&](const float (&fq)[VEC], const float (&fp)[VEC], uint32_t c, bool valid) {
+        const float mq = max_of<VEC>(fq), mp = max_of<VEC>(fp);
+        const bool pq = valid && (mq >= sq.tauv);
+        const bool pp = valid && (mp >= sp.tauv);
+        if (__ballot(pq || pp)) {
+            offer_chunk<KT, C, NS>(sq, s_desc[0], mq, c, pq, k);
+            offer_chunk<KT, C, NS>(sp, s_desc[1], mp, c, pp, k);
+        }
+        sq.s += sum_exp2<VEC>(fq, sq.M2);
+        sp.s += sum_exp2<VEC>(fp, sp.M2);
+    };
+
+    // ---- streaming sweep: iterations in which every lane owns a full 16-byte chunk ----------
+    if (nit > 0) {
+        uint4 wq = vq[lane], wp = vp[lane];
+        for (uint32_t it = 0; it < nit; ++it) {
+            const uint32_t c = it * WAVE + lane;
+            uint4 nq = wq, np = wp;
+            if (it + 1 < nit) {
+                nq = vq[c + WAVE];
+                np = vp[c + WAVE];
+            }
+            float fq[VEC], fp[VEC];
+            ET::unpack(wq, fq);
+            ET::unpack(wp, fp);
+            consume(fq, fp, c, true);
+            wq = nq;
+            wp = np;
+        }
+    }
+    // ---- remainder: fewer than 64 chunks, the last of which may be ragged ------------------------
+    {
+        const uint32_t c = nit * WAVE + lane;
+        if (nit * WAVE < nchunks) {
+            float fq[VEC], fp[VEC];
+            const bool valid = c < nchunks;
+            if (valid) {
+                load_chunk<ET>(rowq, c, nfull, tail, fq);
+                load_chunk<ET>(rowp, c, nfull, tail, fp);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) { fq[j] = neg_inf(); fp[j] = neg_inf(); }
+            }
+            consume(fq, fp, c, valid);
+        }
+    }
+
+    // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
+    const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
+    const double lse_q = ((double)sq.M2 + log2(Sq)) * LN2_D;
+    const double lse_p = ((double)sp.M2 + log2(Sp)) * LN2_D;
+    const double ln_lambda = log((double)A.lambda);
+
+    const double lq_x = (double)ET::load1(rowq, x), lp_x = (double)ET::load1(rowp, x);
+    const double logq_x = lq_x - lse_q, logp_x = lp_x - lse_p;
+    const double logratio = logp_x - logq_x;
+    double acc = exp(logratio - ln_lambda);
+    acc = acc < 1.0 ? acc : 1.0;
+    const bool finite_row = isfinite(lse_q) && isfinite(lse_p) && isfinite(logratio);
+
+    // ---- top-k of both rows: k best chunks -> their elements -> rank by (value desc, id asc) ----
+    Key kth[2];
+    int nc[2];
+    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc[0], sq.cnt, k, true, 0, kth[0]));
+    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc[1], sp.cnt, k, true, 0, kth[1]));
+
+    int nl[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const char *rowA = i == 0 ? rowq : rowp;
+        const char *rowB = i == 0 ? rowp : rowq;
+        const uint32_t thr_ord = (nc[i] >= k) ? KT::ord(uniform_key<Key>(kth[i])) : 0u;
+        int nS = 0;
+
+        // Rank the nS buffered candidates; the best min(nS, k) go to list i in rank order.
+        auto rank_to_list = [&]() {
+            lds_sync();
+            uint64_t mykey[ES];
+            int rank[ES];
+#pragma unroll
+            for (int s = 0; s < ES; ++s) {
+                int e = s * WAVE + lane;
+                mykey[s] = (e < nS) ? (((uint64_t)s_ord[e] << 32) | (uint64_t)(0xffffffffu - s_id[e])) : ~(uint64_t)0;
+                rank[s] = 0;
+            }
+            for (int j = 0; j < nS; ++j) {
+                uint64_t kj = ((uint64_t)s_ord[j] << 32) | (uint64_t)(0xffffffffu - s_id[j]);
+#pragma unroll
+                for (int s = 0; s < ES; ++s) rank[s] += (kj > mykey[s]) ? 1 : 0;
+            }
+#pragma unroll
+            for (int s = 0; s < ES; ++s) {
+                int e = s * WAVE + lane;
+                if (e < nS && rank[s] < k) {
+                    l_id[i][rank[s]] = s_id[e];
+                    l_a[i][rank[s]] = unord32(s_ord[e]);
+                    l_b[i][rank[s]] = __uint_as_float(s_oth[e]);
+                }
+            }
+            lds_sync();
+        };
+
+        for (int base = 0; base < nc[i]; base += WAVE) {
+            const bool has = base + lane < nc[i];
+            const uint32_t c = has ? KT::chunk(s_desc[i][base + lane]) : 0u;
+            float fa[VEC], fb[VEC];
+            if (has) {
+                load_chunk<ET>(rowA, c, nfull, tail, fa);
+                load_chunk<ET>(rowB, c, nfull, tail, fb);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) { fa[j] = neg_inf(); fb[j] = neg_inf(); }
+            }
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                if (nS + WAVE > E) {          // make room: keep only the k best so far
+                    rank_to_list();
+                    const int keep = nS < k ? nS : k;
+                    for (int r = lane; r < keep; r += WAVE) {
+                        s_ord[r] = ord32(l_a[i][r]);
+                        s_id[r] = l_id[i][r];
+                        s_oth[r] = __float_as_uint(l_b[i][r]);
+                    }
+                    nS = keep;
+                    lds_sync();
+                }
+                const int64_t id = (int64_t)c * VEC + j;
+                const uint32_t o = ord32(fa[j]);
+                const bool ok = has && id < V && o >= thr_ord;
+                const uint64_t m = __ballot(ok);
+                if (ok) {
+                    const int pos = nS + lane_prefix(m);
+                    s_ord[pos] = o;
+                    s_id[pos] = (uint32_t)id;
+                    s_oth[pos] = __float_as_uint(fb[j]);
+                }
+                nS += __popcll(m);
+            }
+        }
+        rank_to_list();
+        nl[i] = nS < k ? nS : k;
+    }
+
+    // ---- V_k = union of the two lists; Z_approx = sum over V_k of min(q, p/lambda) -------------
+    // In the log domain min(q, p/lambda) = exp(min(lq - LSEq, lp - LSEp - ln lambda)).
+    double zsum = 0.0;
+    int ucount = 0;
+    for (int r = lane; r < nl[0]; r += WAVE) {
+        const double dq = (double)l_a[0][r] - lse_q;
+        const double dp = (double)l_b[0][r] - lse_p - ln_lambda;
+        zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
+        ucount += 1;
+        if (A.topk_a) A.topk_a[t * k + r] = (int32_t)l_id[0][r];
+        if (A.topk_a_lq) A.topk_a_lq[t * k + r] = finite_row ? (float)dq : NaN;
+    }
+    for (int r = lane; r < nl[1]; r += WAVE) {
+        const uint32_t id = l_id[1][r];
+        bool dup = false;
+        for (int j = 0; j < nl[0]; ++j) dup |= (l_id[0][j] == id);
+        const double dp0 = (double)l_a[1][r] - lse_p;
+        const double dq = (double)l_b[1][r] - lse_q;
+        const double dp = dp0 - ln_lambda;
+        if (!dup) {
+            zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
+            ucount += 1;
+        }
+        if (A.topk_p) A.topk_p[t * k + r] = (int32_t)id;
+        if (A.topk_p_lp) A.topk_p_lp[t * k + r] = finite_row ? (float)dp0 : NaN;
+    }
+    const double z_approx = wave_sum(zsum);
+    const int usize = wave_sum_i(ucount);
+
+    if (lane == 0) {
+        A.rowflag[t] = finite_row ? ROW_OK : ROW_NONFINITE;
+        A.lse_q[t] = lse_q;
+        A.lse_p[t] = lse_p;
+        A.logq[t] = finite_row ? (float)logq_x : NaN;
+        A.logp[t] = finite_row ? (float)logp_x : NaN;
+        A.logratio[t] = finite_row ? (float)logratio : NaN;
+        A.accept[t] = finite_row ? (float)acc : NaN;
+        A.zapprox[t] = finite_row ? (float)z_approx : NaN;
+        if (A.mask) A.mask[t] = (finite_row && A.uni && (double)A.uni[t] < acc) ? 1 : 0;
+        if (A.usize) A.usize[t] = usize;
+    }
+}
+
+// =================================================================================================
+// Exact normaliser (diagnostic): Z_t = sum_v min(q_v, p_v/lambda) = sum_v 2^min(aq_v, ap_v) with
+// aq = (lq - LSEq) log2e, ap = (lp - LSEp - ln lambda) log2e.  One wavefront per row.
+// =================================================================================================
+template <class ET>
+__global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
+{
+    constexpr int VEC = ET::VEC;
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const uint8_t flag = A.rowflag[t];
+    if (flag != ROW_OK) {
+        if (lane == 0) A.zexact[t] = (flag == ROW_PADDING) ? 0.f : __uint_as_float(0x7fc00000u);
+        return;
+    }
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const int64_t V = A.V;
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
+    const float Aq = (float)(A.lse_q[t] * LOG2E_D);
+    const float Ap = (float)((A.lse_p[t] + log((double)A.lambda)) * LOG2E_D);
+    float s0 = 0.f, s1 = 0.f;
+    for (uint32_t c = lane; c < nchunks; c += WAVE) {
+        float fq[VEC], fp[VEC];
+        load_chunk<ET>(rowq, c, nfull, tail, fq);
+        load_chunk<ET>(rowp, c, nfull, tail, fp);
+#pragma unroll
+        for (int j = 0; j < VEC; j += 2) {
+            s0 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j], LOG2E_F, -Aq), __builtin_fmaf(fp[j], LOG2E_F, -Ap)));
+            s1 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j + 1], LOG2E_F, -Aq), __builtin_fmaf(fp[j + 1], LOG2E_F, -Ap)));
+        }
+    }
+    const double Z = wave_sum((double)s0 + (double)s1);
+    if (lane == 0) A.zexact[t] = (float)Z;
+}
+
+// =================================================================================================
+// Batch statistics (Sec. 4.4.2): one workgroup, fixed summation order, so results are
+// bit-reproducible from run to run.
+// =================================================================================================
+constexpr int REDUCE_THREADS = 1024;
+
+__global__ __launch_bounds__(REDUCE_THREADS) void batch_reduce_kernel(FinalizeArgs A)
+{
+    __shared__ double sh_z[REDUCE_THREADS], sh_a[REDUCE_THREADS], sh_ze[REDUCE_THREADS];
+    __shared__ long long sh_n[REDUCE_THREADS], sh_acc[REDUCE_THREADS];
+    __shared__ unsigned sh_err[REDUCE_THREADS];
+    const int tid = threadIdx.x;
+    double z = 0.0, a = 0.0, ze = 0.0;
+    long long n = 0, nacc = 0;
+    unsigned err = 0;
+    for (int64_t t = tid; t < A.T; t += REDUCE_THREADS) {
+        const uint8_t f = A.rowflag[t];
+        if (f == ROW_OK) {
+            n += 1;
+            nacc += A.mask ? (long long)A.mask[t] : 0;
+            z += (double)A.zapprox[t];
+            a += (double)A.accept[t];
+            if (A.zexact) ze += (double)A.zexact[t];
+        } else if (f == ROW_BAD_ID) {
+            err |= JP_DATA_ERR_ID_RANGE;
+        } else if (f == ROW_NONFINITE) {
+            err |= JP_DATA_ERR_NONFINITE;
+        }
+    }
+    sh_z[tid] = z; sh_a[tid] = a; sh_ze[tid] = ze; sh_n[tid] = n; sh_acc[tid] = nacc; sh_err[tid] = err;
+    __syncthreads();
+    for (int o = REDUCE_THREADS / 2; o > 0; o >>= 1) {
+        if (tid < o) {
+            sh_z[tid] += sh_z[tid + o]; sh_a[tid] += sh_a[tid + o]; sh_ze[tid] += sh_ze[tid + o];
+            sh_n[tid] += sh_n[tid + o]; sh_acc[tid] += sh_acc[tid + o]; sh_err[tid] |= sh_err[tid + o];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        jp_obrs_stats st;
+        const double nn = (double)sh_n[0];
+        st.n_valid = sh_n[0];
+        st.n_accept = sh_acc[0];
+        st.mean_z_approx = sh_z[0] / nn;
+        st.mean_accept = sh_a[0] / nn;
+        st.mean_z_exact = A.zexact ? sh_ze[0] / nn : __longlong_as_double(0x7ff8000000000000LL);
+        st.alpha_hat = A.alpha_expected ? st.mean_accept : (double)sh_acc[0] / nn;
+        st.kappa = st.alpha_hat / st.mean_z_approx;
+        st.error_flags = sh_err[0] | (sh_n[0] == 0 ? (unsigned)JP_DATA_ERR_EMPTY : 0u);
+        st.reserved = 0;
+        *A.stats = st;
+    }
+}
+
+// Weights of Alg. 1 step 3:  Z_t = kappa Z_approx,t;  w_t = Z_t max(lambda, p(x)/q(x));
+// rho_t = min(w_t, c1) * min(p_ref(x)/p(x), c2).
+__global__ __launch_bounds__(256) void weights_kernel(FinalizeArgs A)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= A.T) return;
+    const uint8_t f = A.rowflag[t];
+    float w, rho;
+    if (f == ROW_PADDING) {
+        w = 0.f; rho = 0.f;
+    } else if (f != ROW_OK) {
+        w = rho = __uint_as_float(0x7fc00000u);
+    } else {
+        const double kappa = A.stats->kappa;
+        const double zt = kappa * (double)A.zapprox[t];
+        const double ratio = exp((double)A.logratio[t]);
+        const double lam = (double)A.lambda;
+        const double wd = zt * (lam > ratio ? lam : ratio);
+        double rd = wd < (double)A.c1 ? wd : (double)A.c1;
+        if (A.ref_logprob) {
+            const double rr = exp((double)A.ref_logprob[t] - (double)A.logp[t]);
+            rd *= rr < (double)A.c2 ? rr : (double)A.c2;
+        }
+        w = (float)wd; rho = (float)rd;
+    }
+    if (A.w) A.w[t] = w;
+    if (A.rho) A.rho[t] = rho;
+}
+
+// ---- launchers ------------------------------------------------------------------------------
+
+template <class ET, class KT>
+static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<ET, KT, 256>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    if (dtype == JP_BF16) {
+        const int64_t nchunks = (a.V + Bf16Elem::VEC - 1) / Bf16Elem::VEC;
+        if (nchunks <= 65535) return launch_rows_k<Bf16Elem, Key32>(a, st);
+        return launch_rows_k<Bf16Elem, Key64>(a, st);
+    }
+    return launch_rows_k<F32Elem, Key64>(a, st);
+}
+
+hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (dtype == JP_BF16) hipLaunchKernelGGL((zexact_kernel<Bf16Elem>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((zexact_kernel<F32Elem>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
+{
+    hipLaunchKernelGGL(batch_reduce_kernel, dim3(1), dim3(REDUCE_THREADS), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.T <= 0 || (!a.w && !a.rho)) return e;
+    const unsigned blocks = (unsigned)((a.T + 255) / 256);
+    hipLaunchKernelGGL(weights_kernel, dim3(blocks), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace jp

@@ -1,0 +1,207 @@
+"""Thin binding of the C-ABI library ``libjp_obrs.so`` (see ``include/jp_obrs.h``).
+
+Argument marshalling only: torch supplies device memory and the stream handle, every step of
+the path runs in the HIP kernels.  There is no CPU or PyTorch fallback: if the built library is
+missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libjp_obrs.so")
+
+JP_K_MAX = 256
+JP_F32, JP_BF16 = 0, 1
+JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED = 1, 2, 4
+JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
+(JP_OK, JP_ERR_NULL, JP_ERR_SHAPE, JP_ERR_PARAM, JP_ERR_ALIGN, JP_ERR_WORKSPACE,
+ JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
+
+EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
+           "jp_status_string", "jp_obrs_abi_version")
+
+
+class Params(C.Structure):
+    _fields_ = [("lambda_", C.c_float), ("k", C.c_int32), ("c1", C.c_float), ("c2", C.c_float),
+                ("flags", C.c_uint32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("n_valid", C.c_int64), ("n_accept", C.c_int64), ("alpha_hat", C.c_double),
+                ("mean_z_approx", C.c_double), ("kappa", C.c_double), ("mean_z_exact", C.c_double),
+                ("mean_accept", C.c_double), ("error_flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+_OUT_FIELDS = ("accept_prob", "mask", "logq", "logp", "logratio", "z_approx", "z_exact", "w_obrs",
+               "rho", "union_size", "topk_actor", "topk_policy", "topk_actor_logq",
+               "topk_policy_logp", "stats")
+
+
+class Outputs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _OUT_FIELDS]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first "
+        "(python -c 'import __graft_entry__ as g; g.build()').  There is no fallback path.")
+
+_lib = C.CDLL(LIB_PATH)
+_lib.jp_obrs_workspace_bytes.restype = C.c_size_t
+_lib.jp_obrs_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int, C.c_uint32]
+_lib.jp_obrs_forward.restype = C.c_int
+_lib.jp_obrs_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params),
+                                 C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_rows.restype = C.c_int
+_lib.jp_obrs_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                              C.c_void_p, C.c_void_p, C.POINTER(Params), C.POINTER(Outputs),
+                              C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_finalize.restype = C.c_int
+_lib.jp_obrs_finalize.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(Params),
+                                  C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_status_string.restype = C.c_char_p
+_lib.jp_status_string.argtypes = [C.c_int]
+_lib.jp_obrs_abi_version.restype = C.c_int
+
+
+class JpError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"jp_obrs status {status}: {jp_status_string(status)}")
+
+
+def jp_status_string(status: int) -> str:
+    return _lib.jp_status_string(int(status)).decode()
+
+
+def jp_obrs_abi_version() -> int:
+    return _lib.jp_obrs_abi_version()
+
+
+def jp_obrs_workspace_bytes(T: int, V: int, k: int, dt: int, flags: int = 0) -> int:
+    return _lib.jp_obrs_workspace_bytes(T, V, k, dt, flags)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return JP_BF16
+    if t.dtype == torch.float32:
+        return JP_F32
+    raise TypeError(f"logits must be bfloat16 or float32, got {t.dtype}")
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream) -> C.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class Buffers:
+    """Device buffers of one call: the output struct, its tensors and the workspace."""
+    out: Outputs
+    tensors: dict
+    workspace: torch.Tensor
+
+    def __getattr__(self, name):
+        t = self.__dict__.get("tensors", {})
+        if name in t:
+            return t[name]
+        raise AttributeError(name)
+
+    def stats(self) -> Stats:
+        """Copy the device stats struct to the host (synchronises)."""
+        raw = self.tensors["stats"].cpu().numpy().tobytes()
+        return Stats.from_buffer_copy(raw)
+
+
+def alloc_buffers(T: int, V: int, k: int, dt: int, flags: int, device, want=None) -> Buffers:
+    """Allocate outputs + workspace with torch.  ``want``: iterable of output names (default all)."""
+    names = set(_OUT_FIELDS if want is None else want)
+    f32 = dict(dtype=torch.float32, device=device)
+    t = {}
+    for n in ("accept_prob", "logq", "logp", "logratio", "z_approx", "w_obrs", "rho"):
+        if n in names:
+            t[n] = torch.empty(T, **f32)
+    if "z_exact" in names and (flags & JP_FLAG_EXACT_Z):
+        t["z_exact"] = torch.empty(T, **f32)
+    if "mask" in names:
+        t["mask"] = torch.empty(T, dtype=torch.uint8, device=device)
+    if "union_size" in names:
+        t["union_size"] = torch.empty(T, dtype=torch.int32, device=device)
+    for n in ("topk_actor", "topk_policy"):
+        if n in names:
+            t[n] = torch.empty((T, k), dtype=torch.int32, device=device)
+    if flags & JP_FLAG_TOPK_LOGPROBS:
+        for n in ("topk_actor_logq", "topk_policy_logp"):
+            if n in names:
+                t[n] = torch.empty((T, k), **f32)
+    if "stats" in names:
+        t["stats"] = torch.zeros(C.sizeof(Stats), dtype=torch.uint8, device=device)
+    out = Outputs(**{n: (t[n].data_ptr() if n in t else None) for n in _OUT_FIELDS})
+    nbytes = jp_obrs_workspace_bytes(T, V, k, dt, flags)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return Buffers(out, t, ws)
+
+
+def _logit_args(actor: torch.Tensor, policy: torch.Tensor):
+    if actor.dim() != 2 or actor.shape != policy.shape or actor.dtype != policy.dtype:
+        raise ValueError("actor/policy logits must be two [T, V] tensors of one dtype")
+    if actor.stride(1) != 1 or policy.stride(1) != 1 or actor.stride(0) != policy.stride(0):
+        raise ValueError("logit rows must be contiguous and both tensors must share one row stride")
+    T, V = actor.shape
+    return T, V, actor.stride(0) if T > 1 else max(actor.stride(0), V), _dtype_code(actor)
+
+
+def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c1, c2, flags,
+                    buf: Buffers, stream=None) -> None:
+    """Whole hot path on ``stream`` (default: torch's current stream).  Raises JpError on failure."""
+    T, V, stride, dt = _logit_args(actor, policy)
+    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    st = _lib.jp_obrs_forward(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
+                              _p(ref_logprob), C.byref(prm), C.byref(buf.out), _p(buf.workspace),
+                              buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_rows(actor, policy, sampled_ids, uniforms, lam, k, flags, buf: Buffers, stream=None) -> None:
+    T, V, stride, dt = _logit_args(actor, policy)
+    prm = Params(float(lam), int(k), 1.0, 1.0, int(flags))
+    st = _lib.jp_obrs_rows(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
+                           C.byref(prm), C.byref(buf.out), _p(buf.workspace), buf.workspace.numel(),
+                           _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_finalize(T, sampled_ids, ref_logprob, lam, k, c1, c2, flags, buf: Buffers, stream=None) -> None:
+    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    st = _lib.jp_obrs_finalize(int(T), _p(sampled_ids), _p(ref_logprob), C.byref(prm), C.byref(buf.out),
+                               _p(buf.workspace), buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def raw():
+    """The ctypes library handle, for tests of the C ABI itself."""
+    return _lib
+
+
+def run_workload(w, flags: int = 0, want=None, stream=None) -> Buffers:
+    """Allocate buffers for a ``workloads.Workload`` and run the whole hot path on it."""
+    T, V, _, dt = _logit_args(w.actor, w.policy)
+    buf = alloc_buffers(T, V, w.k, dt, flags, w.actor.device, want)
+    jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, w.ref_logprob, w.lam, w.k, w.c1,
+                    w.c2, flags, buf, stream)
+    return buf

@@ -1,0 +1,97 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and turns invalid arguments into status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "jp_obrs.h")
+
+obrs = pytest.importorskip("paper_2602_06107_amd.obrs", reason="HIP library not built")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(jp_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize", "jp_obrs_workspace_bytes",
+            "jp_status_string", "jp_obrs_abi_version"} <= set(names)
+    lib = obrs.raw()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(obrs.EXPORTS) == set(names)
+    assert obrs.jp_obrs_abi_version() == 1
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(obrs.Params) == 20
+    assert C.sizeof(obrs.Stats) == 64
+    assert C.sizeof(obrs.Outputs) == 15 * C.sizeof(C.c_void_p)
+
+
+def test_workspace_bytes():
+    f = obrs.jp_obrs_workspace_bytes
+    assert f(0, 1024, 4, obrs.JP_F32) > 0
+    assert f(8192, 151936, 64, obrs.JP_BF16) >= 8192 * (6 * 4 + 2 * 8 + 2)
+    assert f(8192, 151936, 64, obrs.JP_BF16) < 8192 * 64
+    assert f(-1, 10, 1, obrs.JP_F32) == 0 and f(4, 0, 1, obrs.JP_F32) == 0 and f(4, 10, 1, 7) == 0
+
+
+def _call(actor=0x10000, policy=0x20000, T=4, V=1024, stride=1024, dt=None, ids=0x30000, uni=0x40000,
+          ref=None, lam=1.0, k=8, c1=3.0, c2=3.0, flags=0, ws=0x100000, ws_bytes=1 << 20, out=None,
+          prm_null=False):
+    """Calls jp_obrs_forward with fake (never dereferenced) device addresses: every case below must
+    be rejected by host-side validation, so nothing is launched."""
+    lib = obrs.raw()
+    dt = obrs.JP_F32 if dt is None else dt
+    prm = obrs.Params(lam, k, c1, c2, flags)
+    o = obrs.Outputs() if out is None else out
+    return lib.jp_obrs_forward(actor, policy, T, V, stride, dt, ids, uni, ref,
+                               None if prm_null else C.byref(prm), C.byref(o), ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(actor=None), obrs.JP_ERR_NULL),
+    (dict(policy=None), obrs.JP_ERR_NULL),
+    (dict(ids=None), obrs.JP_ERR_NULL),
+    (dict(prm_null=True), obrs.JP_ERR_NULL),
+    (dict(T=-1), obrs.JP_ERR_SHAPE),
+    (dict(V=0), obrs.JP_ERR_SHAPE),
+    (dict(stride=1000), obrs.JP_ERR_SHAPE),
+    (dict(T=1 << 31), obrs.JP_ERR_SHAPE),
+    (dict(dt=5), obrs.JP_ERR_UNSUPPORTED),
+    (dict(flags=64), obrs.JP_ERR_UNSUPPORTED),
+    (dict(lam=0.0), obrs.JP_ERR_PARAM),
+    (dict(lam=-1.0), obrs.JP_ERR_PARAM),
+    (dict(lam=float("nan")), obrs.JP_ERR_PARAM),
+    (dict(lam=float("inf")), obrs.JP_ERR_PARAM),
+    (dict(c1=0.0), obrs.JP_ERR_PARAM),
+    (dict(c2=float("nan")), obrs.JP_ERR_PARAM),
+    (dict(k=0), obrs.JP_ERR_PARAM),
+    (dict(k=2000), obrs.JP_ERR_PARAM),             # k > V
+    (dict(k=257), obrs.JP_ERR_UNSUPPORTED),        # k > JP_K_MAX
+    (dict(actor=0x10004), obrs.JP_ERR_ALIGN),
+    (dict(policy=0x20008), obrs.JP_ERR_ALIGN),
+    (dict(V=1022, stride=1022), obrs.JP_ERR_ALIGN),   # fp32 row pitch 4088 B
+    (dict(dt=1, V=1020, stride=1020), obrs.JP_ERR_ALIGN),  # bf16 row pitch 2040 B
+    (dict(ws=None), obrs.JP_ERR_WORKSPACE),
+    (dict(ws_bytes=16), obrs.JP_ERR_WORKSPACE),
+    (dict(ws=0x100010), obrs.JP_ERR_ALIGN),
+])
+def test_invalid_arguments_are_rejected_before_launch(kw, want):
+    assert _call(**kw) == want
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(8):
+        msg = obrs.jp_status_string(s)
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert obrs.jp_status_string(99) == "unknown status"

@@ -1,0 +1,169 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64 oracle on the same
+seeded inputs.  Sizes are chosen so the oracle finishes in seconds while the row kernel still
+runs many full iterations, a partial iteration and a ragged tail chunk."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2602_06107_amd import obrs
+    from paper_2602_06107_amd import workloads as wl
+    import parity_util as pu
+
+DEV = "cuda"
+ALL_FLAGS = 1 | 2      # exact Z + top-k log-probs
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_tiny_config_fp32():
+    _say("tiny fp32 T=64 V=1024 k=32")
+    w = wl.tiny(DEV)
+    pu.check_all(w, ALL_FLAGS)
+
+
+@pytest.mark.parametrize("lam", [0.5, 1.0, 2.0])
+def test_rollout_shape_bf16_lambda_sweep(lam):
+    _say(f"bf16 T=96 V=151936 k=64 lambda={lam}")
+    w = wl.make_logits(96, wl.QWEN3_VOCAB, torch.bfloat16, seed=wl.BASE_SEED + 1, device=DEV,
+                       noise_sigma=1.0).with_params(lam=lam, k=64)
+    pu.check_all(w, ALL_FLAGS)
+
+
+@pytest.mark.parametrize("k", [1, 16, 20, 64, 65, 128, 200, 256])
+def test_k_sweep_bf16_per_row_noise(k):
+    _say(f"bf16 T=24 V=151936 k={k} sigma_t~U(0.1,3)")
+    w = wl.make_logits(24, wl.QWEN3_VOCAB, torch.bfloat16, seed=wl.BASE_SEED + 3, device=DEV,
+                       noise_sigma_range=(0.1, 3.0)).with_params(k=k)
+    pu.check_all(w, ALL_FLAGS)
+
+
+def test_extreme_mismatch_bf16():
+    _say("bf16 T=48 V=151936 k=128 noise 2.0")
+    w = wl.make_logits(48, wl.QWEN3_VOCAB, torch.bfloat16, seed=wl.BASE_SEED + 2, device=DEV,
+                       noise_sigma=2.0).with_params(k=128)
+    pu.check_all(w, ALL_FLAGS)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [8, 37, 255, 256, 515, 1027, 4100, 33333])
+def test_ragged_shapes(dtype, V):
+    k = min(V, 24)
+    T = 13
+    _say(f"{dtype} T={T} V={V} k={k} padded stride, padding rows")
+    esz = 2 if dtype == torch.bfloat16 else 4
+    stride = (V * esz + 15) // 16 * 16 // esz + 16 // esz * 3
+    w = wl.make_logits(T, V, dtype, seed=1234 + V, device=DEV, actor_sigma=2.0, spikes=min(3, V),
+                       noise_sigma=0.7, pad_every=5, row_stride=stride).with_params(lam=1.3, k=k)
+    w.ref_logprob = -torch.rand(T, device=DEV) * 3.0
+    pu.check_all(w, ALL_FLAGS)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_k_equals_vocab(dtype):
+    V = 256
+    _say(f"{dtype} k=V={V}: the estimate equals the exact normaliser")
+    w = wl.make_logits(9, V, dtype, seed=77, device=DEV, actor_sigma=2.0, spikes=2,
+                       noise_sigma=1.0).with_params(lam=0.8, k=V)
+    buf, R, st = pu.check_all(w, ALL_FLAGS)
+    tol = pu.TOL[dtype]
+    za, ze = buf.z_approx.cpu().numpy(), buf.z_exact.cpu().numpy()
+    np.testing.assert_allclose(za, ze, rtol=tol)
+    assert np.all(buf.union_size.cpu().numpy() == V)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_constant_and_heavily_tied_rows(dtype):
+    _say(f"{dtype} constant rows, few distinct values, -inf entries")
+    T, V, k = 6, 5000, 40
+    a = torch.zeros((T, V), dtype=torch.float32, device=DEV)
+    p = torch.zeros((T, V), dtype=torch.float32, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    a[0] = 1.5; p[0] = -0.25                                             # constant rows
+    a[1] = torch.randint(-2, 3, (V,), generator=g, device=DEV).float()   # five distinct values
+    p[1] = torch.randint(-2, 3, (V,), generator=g, device=DEV).float()
+    a[2] = torch.randn(V, generator=g, device=DEV); p[2] = a[2]          # matched distributions
+    a[3] = torch.randn(V, generator=g, device=DEV); p[3] = a[3] + 0.5 * torch.randn(V, generator=g, device=DEV)
+    a[3, : V // 2] = float("-inf"); p[3, V // 3:] += 2.0                 # masked vocabulary entries
+    a[3, 7] = 3.0; p[3, 100:130] = float("-inf")
+    a[4] = -torch.arange(V, device=DEV).float() * 0.01                   # monotone decreasing
+    p[4] = torch.arange(V, device=DEV).float() * 0.01                    # monotone increasing
+    a[5, :] = float("-inf"); a[5, 4000:4030] = 0.0                       # fewer finite entries than k
+    p[5] = torch.randn(V, generator=g, device=DEV)
+    x = torch.tensor([17, 3, 1000, 4000, 0, 4010], dtype=torch.int32, device=DEV)
+    u = torch.tensor([0.3, 0.6, 0.999, 0.01, 0.5, 0.2], dtype=torch.float32, device=DEV)
+    w = wl.Workload("degenerate", a.to(dtype), p.to(dtype), x, u, lam=2.0, k=k)
+    buf, R, st = pu.check_all(w, ALL_FLAGS)
+    assert buf.topk_actor[0].cpu().tolist() == list(range(k))
+    assert int(buf.union_size[0]) == k
+
+
+def test_rows_plus_finalize_equals_forward_and_is_deterministic():
+    _say("bf16 T=64 V=20000: staged entry points, repeat run")
+    w = wl.make_logits(64, 20000, torch.bfloat16, seed=9, device=DEV).with_params(k=64, lam=1.0)
+    b1 = obrs.run_workload(w, ALL_FLAGS)
+    b2 = obrs.run_workload(w, ALL_FLAGS)
+    T, V = w.T, w.V
+    b3 = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, ALL_FLAGS, DEV)
+    obrs.jp_obrs_rows(w.actor, w.policy, w.sampled_ids, w.uniforms, w.lam, w.k, ALL_FLAGS, b3)
+    obrs.jp_obrs_finalize(T, w.sampled_ids, None, w.lam, w.k, w.c1, w.c2, ALL_FLAGS, b3)
+    torch.cuda.synchronize()
+    for n in b1.tensors:
+        assert torch.equal(b1.tensors[n], b2.tensors[n]), n
+        assert torch.equal(b1.tensors[n], b3.tensors[n]), n
+
+
+def test_expected_alpha_and_missing_uniforms():
+    _say("bf16 T=40 V=9000: alpha_hat := mean a")
+    w = wl.make_logits(40, 9000, torch.bfloat16, seed=10, device=DEV).with_params(k=20)
+    pu.check_all(w, obrs.JP_FLAG_ALPHA_EXPECTED)
+    b1 = obrs.run_workload(w, obrs.JP_FLAG_ALPHA_EXPECTED)
+    buf = obrs.alloc_buffers(w.T, w.V, w.k, obrs.JP_BF16, 0, DEV)
+    obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, None, None, w.lam, w.k, w.c1, w.c2, 0, buf)
+    torch.cuda.synchronize()
+    assert buf.stats().kappa == b1.stats().kappa
+    assert torch.equal(buf.w_obrs, b1.w_obrs)
+    assert int(buf.mask.sum()) == 0
+
+
+def test_device_side_error_flags():
+    _say("fp32 T=8 V=300: bad sampled id, NaN and +inf logits")
+    w = wl.make_logits(8, 300, torch.float32, seed=11, device=DEV, spikes=2).with_params(k=10)
+    w.sampled_ids[2] = 300
+    w.actor[4, 17] = float("nan")
+    w.policy[6, 5] = float("inf")
+    buf = obrs.run_workload(w, ALL_FLAGS)
+    torch.cuda.synchronize()
+    st = buf.stats()
+    assert st.error_flags == (obrs.JP_DATA_ERR_ID_RANGE | obrs.JP_DATA_ERR_NONFINITE)
+    assert st.n_valid == 5
+    bad = [2, 4, 6]
+    good = [0, 1, 3, 5, 7]
+    for n in ("accept_prob", "logq", "logp", "logratio", "z_approx", "z_exact", "w_obrs", "rho"):
+        t = buf.tensors[n].cpu().numpy()
+        assert np.all(np.isnan(t[bad])), n
+        assert np.all(np.isfinite(t[good])), n
+    # the good rows still match the oracle
+    R = pu.run_oracle(w, rows=good)
+    g = {n: t.cpu().numpy()[good] for n, t in buf.tensors.items() if n != "stats"}
+    np.testing.assert_array_equal(g["topk_actor"], R.topk_q)
+    np.testing.assert_allclose(g["z_approx"], R.out["z_approx"], rtol=1e-5)
+
+
+def test_empty_batch_and_all_padding():
+    _say("T=0 and all-padding batches")
+    w = wl.make_logits(4, 128, torch.float32, seed=12, device=DEV, spikes=0).with_params(k=4)
+    w.sampled_ids[:] = -1
+    buf = obrs.run_workload(w)
+    torch.cuda.synchronize()
+    st = buf.stats()
+    assert st.n_valid == 0 and st.error_flags == obrs.JP_DATA_ERR_EMPTY and np.isnan(st.kappa)
+    assert float(buf.w_obrs.abs().sum()) == 0.0
+    w0 = wl.Workload("empty", w.actor[:0], w.policy[:0], w.sampled_ids[:0], w.uniforms[:0], k=4)
+    buf = obrs.run_workload(w0)
+    torch.cuda.synchronize()
+    assert buf.stats().error_flags == obrs.JP_DATA_ERR_EMPTY
