@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Throughput of the OBRS hot path on one MI355X.
+
+A step is one pass of the whole hot path (row stage + batch stage, `jp_obrs_forward`) over one
+batch of seeded synthetic logits that are already resident in HBM.  The workload is the
+Qwen3-1.7B-shaped rollout batch (T=8192 tokens, V=151936, bf16 logits, k=64, lambda=1).
+
+Prints one JSON line: tokens/s for the whole path, the HBM roofline of the dominant kernel (the
+row kernel, timed with HIP events on the launch stream) and the float64 CPU oracle timed on a
+bounded sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "OBRS tokens/sec at V=151936 bf16 on 1 MI355X; achieved HBM GB/s vs peak"
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/), scaled by the counter reading of a plain copy of known size.
+# None until measured for the workload below.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_per_token(V: int, k: int, esz: int) -> int:
+    """Bytes the row stage must move per token: both logit rows once, the sampled id and the
+    uniform, the seven per-token results (a, mask, log q, log p, log-ratio, Z_approx, |V_k|) and
+    the two top-k id lists."""
+    reads = 2 * V * esz + 4 + 4
+    writes = 4 + 1 + 4 + 4 + 4 + 4 + 4 + 2 * k * 4
+    return reads + writes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--tokens", type=int, default=8192, help="T of the rollout batch")
+    ap.add_argument("--k", type=int, default=64)
+    ap.add_argument("--lam", type=float, default=1.0)
+    ap.add_argument("--calibrate-copy", type=int, default=0,
+                    help="also run this many plain device copies of the actor tensor (a kernel of "
+                         "known HBM traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--cpu-rows", type=int, default=4096,
+                    help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; the hot path has no collectives and "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_06107_amd import obrs
+    from paper_2602_06107_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = wl.rollout(dev, T=args.tokens).with_params(lam=args.lam, k=args.k)
+    T, V = w.T, w.V
+    esz = w.actor.element_size()
+    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, 0, dev)
+    torch.cuda.synchronize()
+
+    def step():
+        obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, None, w.lam, w.k, w.c1,
+                             w.c2, 0, buf)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = T * args.steps / wall
+    st = buf.stats()
+
+    # ---- dominant kernel: the row kernel alone, HIP events on the launch stream -----------------
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        obrs.jp_obrs_rows(w.actor, w.policy, w.sampled_ids, w.uniforms, w.lam, w.k, 0, buf)
+        b.record()
+    torch.cuda.synchronize()
+    row_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    row_ms_avg = sum(row_ms) / len(row_ms)
+    algo_bytes = algorithmic_bytes_per_token(V, w.k, esz) * T
+    achieved = algo_bytes / (row_ms_avg * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((T, V, w.k))
+
+    if args.calibrate_copy > 0:
+        scratch = torch.empty_like(w.actor)
+        for _ in range(args.calibrate_copy):
+            scratch.copy_(w.actor)
+        torch.cuda.synchronize()
+        del scratch
+
+    # ---- CPU oracle on a bounded sample of the same batch ---------------------------------------
+    cpu = None
+    if args.cpu_rows > 0:
+        from oracle import obrs_oracle as orc
+        n = min(args.cpu_rows, T)
+        a_np = wl.logits_to_numpy(w.actor[:n])
+        p_np = wl.logits_to_numpy(w.policy[:n])
+        x_np = w.sampled_ids[:n].cpu().numpy()
+        u_np = w.uniforms[:n].cpu().numpy()
+        orc.lib()
+        c0 = time.perf_counter()
+        R = orc.rows(a_np, p_np, x_np, u_np, w.lam, w.k)
+        orc.batch(R.out, R.out["mask"], w.lam, w.c1, w.c2)
+        cw = time.perf_counter() - c0
+        cpu = {"value": n / cw, "unit": "tokens/s", "cores": int(R.threads), "kind": "oracle",
+               "sample": f"first {n} of {T} rows of the same batch, float64 C oracle, "
+                         f"{cw:.1f} s wall"}
+
+    line = {
+        "metric": METRIC,
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "rollout: T=%d (16 seq x 512 tok), V=%d, bf16 logits, k=%d, "
+                               "lambda=%g, c1=c2=3" % (T, V, w.k, w.lam),
+                   "logits_dtype": "bf16", "T": T, "V": V, "k": w.k, "lambda": w.lam,
+                   "kappa": st.kappa, "alpha_hat": st.alpha_hat},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "row_kernel<bf16,key32,64>", "kernel_ms_avg": row_ms_avg,
+                     "kernel_ms_min": row_ms[0], "algorithmic_bytes": algo_bytes},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

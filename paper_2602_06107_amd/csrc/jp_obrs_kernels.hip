@@ -31,6 +31,12 @@ constexpr float M2_UNSET = -3.0e38f;
 
 __device__ __forceinline__ float neg_inf() { return __uint_as_float(0xff800000u); }
 
+// 16 bytes of logits as a native vector (kept in four VGPRs), loaded through the global address
+// space so the compiler emits global_load_dwordx4 and can keep several loads in flight.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+__device__ __forceinline__ gvec_ptr as_global_vec(const void *p) { return (gvec_ptr)(uintptr_t)p; }
+
 // Order-preserving map float -> uint32 (-0 is folded onto +0 so that equal values get equal keys).
 __device__ __forceinline__ uint32_t ord32(float f)
 {
@@ -86,7 +92,7 @@ __device__ __forceinline__ void lds_sync() { __syncthreads(); }
 struct Bf16Elem {
     static constexpr int VEC = 8;           // elements per 16-byte load
     static constexpr int ESZ = 2;
-    static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[VEC])
+    static __device__ __forceinline__ void unpack(const u32x4 w, float (&f)[VEC])
     {
         f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
         f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
@@ -102,7 +108,7 @@ struct Bf16Elem {
 struct F32Elem {
     static constexpr int VEC = 4;
     static constexpr int ESZ = 4;
-    static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[VEC])
+    static __device__ __forceinline__ void unpack(const u32x4 w, float (&f)[VEC])
     {
         f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
         f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
@@ -262,8 +268,7 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
                                            float (&f)[ET::VEC])
 {
     if (c < nfull) {
-        uint4 w = ((const uint4 *)row)[c];
-        ET::unpack(w, f);
+        ET::unpack(as_global_vec(row)[c], f);
     } else {
 #pragma unroll
         for (int j = 0; j < ET::VEC; ++j)
@@ -319,8 +324,8 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
 
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
-    const uint4 *vq = (const uint4 *)rowq;
-    const uint4 *vp = (const uint4 *)rowp;
+    const gvec_ptr vq = as_global_vec(rowq);
+    const gvec_ptr vp = as_global_vec(rowp);
     const uint32_t nfull = (uint32_t)(V / VEC);
     const int tail = (int)(V - (int64_t)nfull * VEC);
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
@@ -343,20 +348,17 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
 
     // ---- streaming sweep: iterations in which every lane owns a full 16-byte chunk ----------
     if (nit > 0) {
-        uint4 wq = vq[lane], wp = vp[lane];
+        u32x4 wq = vq[lane], wp = vp[lane];
         for (uint32_t it = 0; it < nit; ++it) {
             const uint32_t c = it * WAVE + lane;
-            uint4 nq = wq, np = wp;
-            if (it + 1 < nit) {
-                nq = vq[c + WAVE];
-                np = vp[c + WAVE];
-            }
+            const u32x4 cq = wq, cp = wp;
+            const uint32_t cn = (it + 1 < nit) ? c + WAVE : c;     // prefetch the next chunk
+            wq = vq[cn];
+            wp = vp[cn];
             float fq[VEC], fp[VEC];
-            ET::unpack(wq, fq);
-            ET::unpack(wp, fp);
+            ET::unpack(cq, fq);
+            ET::unpack(cp, fp);
             consume(fq, fp, c, true);
-            wq = nq;
-            wp = np;
         }
     }
     // ---- remainder: fewer than 64 chunks, the last of which may be ragged ------------------------
