@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libjp_obrs.so")
+LIB_PATH = os.environ.get("JP_OBRS_LIB", os.path.join(_PKG, "libjp_obrs.so"))   # override: another build of the same ABI
 
 JP_K_MAX = 256
 JP_F32, JP_BF16 = 0, 1
