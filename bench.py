@@ -45,8 +45,8 @@ def main():
     ap.add_argument("--k", type=int, default=64)
     ap.add_argument("--lam", type=float, default=1.0)
     ap.add_argument("--calibrate-copy", type=int, default=0,
-                    help="also run this many plain device copies of the actor tensor (a kernel of "
-                         "known HBM traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+                    help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
+                         "a kernel of known HBM traffic that scales rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -103,7 +103,7 @@ def main():
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)
         for _ in range(args.calibrate_copy):
-            scratch.copy_(w.actor)
+            torch.neg(w.actor, out=scratch)      # elementwise kernel: reads and writes T*V*2 bytes
         torch.cuda.synchronize()
         del scratch
 

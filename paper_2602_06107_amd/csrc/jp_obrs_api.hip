@@ -83,7 +83,7 @@ jp_status rows_impl(const void *actor, const void *policy, int64_t T, int64_t V,
     const Workspace w = carve(workspace, T);
     jp::RowArgs a{};
     a.actor = actor; a.policy = policy; a.T = T; a.V = V; a.stride = row_stride;
-    a.ids = ids; a.uni = uni; a.lambda = prm->lambda; a.k = prm->k;
+    a.ids = ids; a.uni = uni; a.lambda = prm->lambda; a.ln_lambda = log((double)prm->lambda); a.k = prm->k;
     a.accept = out->accept_prob ? out->accept_prob : w.accept;
     a.logq = out->logq ? out->logq : w.logq;
     a.logp = out->logp ? out->logp : w.logp;

@@ -18,6 +18,7 @@ struct RowArgs {
     const int32_t *ids;               // [T]
     const float *uni;                 // [T] or nullptr
     float lambda;
+    double ln_lambda;                 // log(lambda), taken on the host
     int k;
     // per-row results: never nullptr (user buffer or workspace)
     float *accept, *logq, *logp, *logratio, *zapprox;

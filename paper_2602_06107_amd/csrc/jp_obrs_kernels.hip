@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "jp_obrs_internal.h"
 
 namespace jp {
@@ -34,6 +36,7 @@ __device__ __forceinline__ float neg_inf() { return __uint_as_float(0xff800000u)
 // 16 bytes of logits as a native vector (kept in four VGPRs), loaded through the global address
 // space so the compiler emits global_load_dwordx4 and can keep several loads in flight.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
 __device__ __forceinline__ gvec_ptr as_global_vec(const void *p) { return (gvec_ptr)(uintptr_t)p; }
 
@@ -242,6 +245,17 @@ __device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typena
     }
 }
 
+// log2 of a positive float sum: exponent plus hardware log2 of the mantissa in [1, 2), so the
+// absolute error stays near 1e-7 whatever the magnitude.  0 -> -inf, inf/NaN propagate.
+__device__ __forceinline__ double log2_of_sum(double S)
+{
+    const float f = (float)S;
+    if (!(f > 0.f) || !(f < __uint_as_float(0x7f800000u))) return (double)__builtin_amdgcn_logf(f);
+    const int e = __builtin_amdgcn_frexp_expf(f);            // f = m * 2^e, m in [0.5, 1)
+    const float m2 = __builtin_amdgcn_frexp_mantf(f) * 2.0f;
+    return (double)(e - 1) + (double)__builtin_amdgcn_logf(m2);
+}
+
 template <int VEC> __device__ __forceinline__ float max_of(const float (&f)[VEC])
 {
     float m = f[0];
@@ -292,7 +306,8 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
     constexpr int ES = E / WAVE;
 
     __shared__ Key s_desc[2][C];
-    __shared__ uint32_t s_ord[E], s_id[E], s_oth[E];
+    __shared__ __attribute__((aligned(16))) uint64_t s_key[E + 2];   // (ord32(value) << 32) | ~id
+    __shared__ uint32_t s_oth[E];                                    // the other tensor's logit
     __shared__ uint32_t l_id[2][KC];
     __shared__ float l_a[2][KC], l_b[2][KC];
 
@@ -348,17 +363,26 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
 
     // ---- streaming sweep: iterations in which every lane owns a full 16-byte chunk ----------
     if (nit > 0) {
-        u32x4 wq = vq[lane], wp = vp[lane];
-        for (uint32_t it = 0; it < nit; ++it) {
-            const uint32_t c = it * WAVE + lane;
-            const u32x4 cq = wq, cp = wp;
-            const uint32_t cn = (it + 1 < nit) ? c + WAVE : c;     // prefetch the next chunk
-            wq = vq[cn];
-            wp = vp[cn];
+        // Two 16-byte loads per tensor stay in flight per lane: the loads for iterations it+2 and
+        // it+3 are issued before iterations it and it+1 are consumed (indices clamp at the end).
+        const uint32_t last = nit - 1;
+        u32x4 wq0 = vq[lane], wp0 = vp[lane];
+        u32x4 wq1 = vq[(last < 1u ? last : 1u) * WAVE + lane], wp1 = vp[(last < 1u ? last : 1u) * WAVE + lane];
+        for (uint32_t it = 0; it < nit; it += 2) {
+            const u32x4 cq0 = wq0, cp0 = wp0, cq1 = wq1, cp1 = wp1;
+            const uint32_t n0 = (it + 2 < last ? it + 2 : last) * WAVE + lane;
+            const uint32_t n1 = (it + 3 < last ? it + 3 : last) * WAVE + lane;
+            wq0 = vq[n0]; wp0 = vp[n0];
+            wq1 = vq[n1]; wp1 = vp[n1];
             float fq[VEC], fp[VEC];
-            ET::unpack(cq, fq);
-            ET::unpack(cp, fp);
-            consume(fq, fp, c, true);
+            ET::unpack(cq0, fq);
+            ET::unpack(cp0, fp);
+            consume(fq, fp, it * WAVE + lane, true);
+            if (it + 1 < nit) {
+                ET::unpack(cq1, fq);
+                ET::unpack(cp1, fp);
+                consume(fq, fp, (it + 1) * WAVE + lane, true);
+            }
         }
     }
     // ---- remainder: fewer than 64 chunks, the last of which may be ragged ------------------------
@@ -379,23 +403,26 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
     }
 
     // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
-    const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
-    const double lse_q = ((double)sq.M2 + log2(Sq)) * LN2_D;
-    const double lse_p = ((double)sp.M2 + log2(Sp)) * LN2_D;
-    const double ln_lambda = log((double)A.lambda);
+    const double lse_q = ((double)sq.M2 + log2_of_sum(wave_sum((double)sq.s))) * LN2_D;
+    const double lse_p = ((double)sp.M2 + log2_of_sum(wave_sum((double)sp.s))) * LN2_D;
+    const double ln_lambda = A.ln_lambda;
 
     const double lq_x = (double)ET::load1(rowq, x), lp_x = (double)ET::load1(rowp, x);
     const double logq_x = lq_x - lse_q, logp_x = lp_x - lse_p;
     const double logratio = logp_x - logq_x;
-    double acc = exp(logratio - ln_lambda);
+    // a = min(1, p(x) / (lambda q(x))), taken in the log2 domain
+    double acc = (double)__builtin_amdgcn_exp2f((float)((logratio - ln_lambda) * LOG2E_D));
     acc = acc < 1.0 ? acc : 1.0;
     const bool finite_row = isfinite(lse_q) && isfinite(lse_p) && isfinite(logratio);
 
     // ---- top-k of both rows: k best chunks -> their elements -> rank by (value desc, id asc) ----
     Key kth[2];
     int nc[2];
-    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc[0], sq.cnt, k, true, 0, kth[0]));
-    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc[1], sp.cnt, k, true, 0, kth[1]));
+    // The value bits of the k-th largest chunk maximum are enough: every chunk at or above that
+    // value is expanded and the element ranking below is exact.  Only a large plateau of equal
+    // maxima makes the select run to the last bit (leaving exactly k chunks).
+    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc[0], sq.cnt, k, false, 2 * KC, kth[0]));
+    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc[1], sp.cnt, k, false, 2 * KC, kth[1]));
 
     int nl[2];
 #pragma unroll
@@ -406,30 +433,37 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
         int nS = 0;
 
         // Rank the nS buffered candidates; the best min(nS, k) go to list i in rank order.
-        auto rank_to_list = [&]() {
-            lds_sync();
-            uint64_t mykey[ES];
-            int rank[ES];
+        auto rank_slots = [&](auto nslots_c) {
+            constexpr int N = decltype(nslots_c)::value;
+            uint64_t mykey[N];
+            int rank[N];
 #pragma unroll
-            for (int s = 0; s < ES; ++s) {
-                int e = s * WAVE + lane;
-                mykey[s] = (e < nS) ? (((uint64_t)s_ord[e] << 32) | (uint64_t)(0xffffffffu - s_id[e])) : ~(uint64_t)0;
+            for (int s = 0; s < N; ++s) {
+                const int e = s * WAVE + lane;
+                mykey[s] = (e < nS) ? s_key[e] : ~(uint64_t)0;
                 rank[s] = 0;
             }
-            for (int j = 0; j < nS; ++j) {
-                uint64_t kj = ((uint64_t)s_ord[j] << 32) | (uint64_t)(0xffffffffu - s_id[j]);
+            for (int j = 0; j < nS; j += 2) {          // s_key[nS] is a zero pad
+                const u64x2 kj = *(const u64x2 *)&s_key[j];
 #pragma unroll
-                for (int s = 0; s < ES; ++s) rank[s] += (kj > mykey[s]) ? 1 : 0;
+                for (int s = 0; s < N; ++s) rank[s] += (kj.x > mykey[s] ? 1 : 0) + (kj.y > mykey[s] ? 1 : 0);
             }
 #pragma unroll
-            for (int s = 0; s < ES; ++s) {
-                int e = s * WAVE + lane;
+            for (int s = 0; s < N; ++s) {
+                const int e = s * WAVE + lane;
                 if (e < nS && rank[s] < k) {
-                    l_id[i][rank[s]] = s_id[e];
-                    l_a[i][rank[s]] = unord32(s_ord[e]);
+                    l_id[i][rank[s]] = 0xffffffffu - (uint32_t)mykey[s];
+                    l_a[i][rank[s]] = unord32((uint32_t)(mykey[s] >> 32));
                     l_b[i][rank[s]] = __uint_as_float(s_oth[e]);
                 }
             }
+        };
+        auto rank_to_list = [&]() {
+            if (lane == 0) s_key[nS] = 0;
+            lds_sync();
+            if (nS <= WAVE) rank_slots(std::integral_constant<int, 1>{});
+            else if (nS <= 2 * WAVE) rank_slots(std::integral_constant<int, 2>{});
+            else rank_slots(std::integral_constant<int, ES>{});
             lds_sync();
         };
 
@@ -450,8 +484,7 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
                     rank_to_list();
                     const int keep = nS < k ? nS : k;
                     for (int r = lane; r < keep; r += WAVE) {
-                        s_ord[r] = ord32(l_a[i][r]);
-                        s_id[r] = l_id[i][r];
+                        s_key[r] = ((uint64_t)ord32(l_a[i][r]) << 32) | (uint64_t)(0xffffffffu - l_id[i][r]);
                         s_oth[r] = __float_as_uint(l_b[i][r]);
                     }
                     nS = keep;
@@ -463,8 +496,7 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
                 const uint64_t m = __ballot(ok);
                 if (ok) {
                     const int pos = nS + lane_prefix(m);
-                    s_ord[pos] = o;
-                    s_id[pos] = (uint32_t)id;
+                    s_key[pos] = ((uint64_t)o << 32) | (uint64_t)(0xffffffffu - (uint32_t)id);
                     s_oth[pos] = __float_as_uint(fb[j]);
                 }
                 nS += __popcll(m);
