@@ -296,7 +296,7 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // Row kernel: S1-S5 of the hot path for one token position per wavefront.
 // =================================================================================================
 template <class ET, class KT, int KC>
-__global__ __launch_bounds__(64) void row_kernel(RowArgs A)
+__global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
@@ -305,9 +305,17 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
     constexpr int E = 2 * KC + WAVE;      // element candidate capacity
     constexpr int ES = E / WAVE;
 
-    __shared__ Key s_desc[2][C];
-    __shared__ __attribute__((aligned(16))) uint64_t s_key[E + 2];   // (ord32(value) << 32) | ~id
-    __shared__ uint32_t s_oth[E];                                    // the other tensor's logit
+    // One LDS pool, used twice: during the sweep it holds the two descriptor buffers; once the
+    // surviving descriptors sit in registers it holds the element candidates of the expansion.
+    constexpr int DS = 2 * KC / WAVE;                               // descriptor registers per lane
+    constexpr int DESC_BYTES = 2 * C * (int)sizeof(Key);
+    constexpr int CAND_BYTES = (E + 2) * 8 + E * 4;
+    constexpr int POOL_BYTES = ((DESC_BYTES > CAND_BYTES ? DESC_BYTES : CAND_BYTES) + 15) / 16 * 16;
+    __shared__ __attribute__((aligned(16))) unsigned char pool[POOL_BYTES];
+    Key *const s_desc0 = (Key *)pool;
+    Key *const s_desc1 = s_desc0 + C;
+    uint64_t *const s_key = (uint64_t *)pool;                       // (ord32(value) << 32) | ~id
+    uint32_t *const s_oth = (uint32_t *)(pool + (E + 2) * 8);       // the other tensor's logit
     __shared__ uint32_t l_id[2][KC];
     __shared__ float l_a[2][KC], l_b[2][KC];
 
@@ -354,8 +362,8 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
         const bool pq = valid && (mq >= sq.tauv);
         const bool pp = valid && (mp >= sp.tauv);
         if (__ballot(pq || pp)) {
-            offer_chunk<KT, C, NS>(sq, s_desc[0], mq, c, pq, k);
-            offer_chunk<KT, C, NS>(sp, s_desc[1], mp, c, pp, k);
+            offer_chunk<KT, C, NS>(sq, s_desc0, mq, c, pq, k);
+            offer_chunk<KT, C, NS>(sp, s_desc1, mp, c, pp, k);
         }
         sq.s += sum_exp2<VEC>(fq, sq.M2);
         sp.s += sum_exp2<VEC>(fp, sp.M2);
@@ -421,12 +429,20 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
     // The value bits of the k-th largest chunk maximum are enough: every chunk at or above that
     // value is expanded and the element ranking below is exact.  Only a large plateau of equal
     // maxima makes the select run to the last bit (leaving exactly k chunks).
-    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc[0], sq.cnt, k, false, 2 * KC, kth[0]));
-    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc[1], sp.cnt, k, false, 2 * KC, kth[1]));
+    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, 2 * KC, kth[0]));
+    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc1, sp.cnt, k, false, 2 * KC, kth[1]));
+    Key dk[2][DS];                                                  // at most 2*KC survive per tensor
+#pragma unroll
+    for (int sl = 0; sl < DS; ++sl) {
+        const int e = sl * WAVE + lane;
+        dk[0][sl] = e < nc[0] ? s_desc0[e] : (Key)0;
+        dk[1][sl] = e < nc[1] ? s_desc1[e] : (Key)0;
+    }
+    lds_sync();                                                     // the pool now belongs to the candidates
 
     int nl[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    auto expand = [&](auto tensor_c) {
+        constexpr int i = decltype(tensor_c)::value;
         const char *rowA = i == 0 ? rowq : rowp;
         const char *rowB = i == 0 ? rowp : rowq;
         const uint32_t thr_ord = (nc[i] >= k) ? KT::ord(uniform_key<Key>(kth[i])) : 0u;
@@ -467,9 +483,11 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
             lds_sync();
         };
 
-        for (int base = 0; base < nc[i]; base += WAVE) {
-            const bool has = base + lane < nc[i];
-            const uint32_t c = has ? KT::chunk(s_desc[i][base + lane]) : 0u;
+#pragma unroll
+        for (int sl = 0; sl < DS; ++sl) {
+            if (sl * WAVE >= nc[i]) break;
+            const bool has = sl * WAVE + lane < nc[i];
+            const uint32_t c = has ? KT::chunk(dk[i][sl]) : 0u;
             float fa[VEC], fb[VEC];
             if (has) {
                 load_chunk<ET>(rowA, c, nfull, tail, fa);
@@ -504,7 +522,9 @@ __global__ __launch_bounds__(64) void row_kernel(RowArgs A)
         }
         rank_to_list();
         nl[i] = nS < k ? nS : k;
-    }
+    };
+    expand(std::integral_constant<int, 0>{});
+    expand(std::integral_constant<int, 1>{});
 
     // ---- V_k = union of the two lists; Z_approx = sum over V_k of min(q, p/lambda) -------------
     // In the log domain min(q, p/lambda) = exp(min(lq - LSEq, lp - LSEp - ln lambda)).
