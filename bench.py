@@ -45,8 +45,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--tokens", type=int, default=8192, help="T of the rollout batch")
-    ap.add_argument("--k", type=int, default=64)
+    ap.add_argument("--workload", choices=["rollout", "training", "long"], default="rollout",
+                    help="rollout (T=8192, k=64) is the configuration the metric is quoted on; the "
+                         "others are for context")
+    ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
+    ap.add_argument("--k", type=int, default=0, help="override k of the workload")
     ap.add_argument("--lam", type=float, default=1.0)
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
@@ -68,7 +71,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    w = wl.rollout(dev, T=args.tokens).with_params(lam=args.lam, k=args.k)
+    make = {"rollout": wl.rollout, "training": wl.training, "long": wl.long_response}[args.workload]
+    w = make(dev, T=args.tokens) if args.tokens > 0 else make(dev)
+    w = w.with_params(lam=args.lam, k=args.k if args.k > 0 else w.k)
     T, V = w.T, w.V
     esz = w.actor.element_size()
     buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, 0, dev)
@@ -142,13 +147,13 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "rollout: T=%d (16 seq x 512 tok), V=%d, bf16 logits, k=%d, "
-                               "lambda=%g, c1=c2=3" % (T, V, w.k, w.lam),
+        "config": {"workload": "%s: T=%d, V=%d, bf16 logits, k=%d, lambda=%g, c1=c2=3"
+                               % (w.name, T, V, w.k, w.lam),
                    "logits_dtype": "bf16", "T": T, "V": V, "k": w.k, "lambda": w.lam,
                    "kappa": st.kappa, "alpha_hat": st.alpha_hat},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "row_kernel<bf16,key32,64>", "kernel_ms_avg": row_ms_avg,
+                     "kernel": "row_kernel<bf16,key32,%d>" % (64 if w.k <= 64 else 128 if w.k <= 128 else 256), "kernel_ms_avg": row_ms_avg,
                      "kernel_ms_min": row_ms[0], "algorithmic_bytes": algo_bytes},
         "cpu_baseline": cpu,
     }

@@ -70,23 +70,61 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
     return ((uint64_t)uniform_u((uint32_t)(v >> 32)) << 32) | uniform_u((uint32_t)v);
 }
 
+// Wave-wide reductions on the VALU (data-parallel primitives, no LDS traffic): butterflies inside
+// each quad (quad_perm), rotations by 4 and 8 inside each row of 16 lanes, then the four row
+// results are read out and combined in a fixed order, so every lane gets the same bits.
+template <int CTRL> __device__ __forceinline__ int dpp_mov(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1, DPP_QUAD_XOR2 = 0x4E, DPP_ROW_ROR4 = 0x124, DPP_ROW_ROR8 = 0x128;
+
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_mov<CTRL>(__float_as_int(v))); }
+template <int CTRL> __device__ __forceinline__ double dpp_d(double v)
+{
+    return __hiloint2double(dpp_mov<CTRL>(__double2hiint(v)), dpp_mov<CTRL>(__double2loint(v)));
+}
+__device__ __forceinline__ double lane_value_d(double v, int l)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l), __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-    return v;
+    v = fmaxf(v, dpp_f<DPP_QUAD_XOR1>(v));
+    v = fmaxf(v, dpp_f<DPP_QUAD_XOR2>(v));
+    v = fmaxf(v, dpp_f<DPP_ROW_ROR4>(v));
+    v = fmaxf(v, dpp_f<DPP_ROW_ROR8>(v));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-    return v;
+    v += dpp_d<DPP_QUAD_XOR1>(v);
+    v += dpp_d<DPP_QUAD_XOR2>(v);
+    v += dpp_d<DPP_ROW_ROR4>(v);
+    v += dpp_d<DPP_ROW_ROR8>(v);
+    return ((lane_value_d(v, 0) + lane_value_d(v, 16)) + lane_value_d(v, 32)) + lane_value_d(v, 48);
 }
 __device__ __forceinline__ int wave_sum_i(int v)
 {
+    v += dpp_mov<DPP_QUAD_XOR1>(v);
+    v += dpp_mov<DPP_QUAD_XOR2>(v);
+    v += dpp_mov<DPP_ROW_ROR4>(v);
+    v += dpp_mov<DPP_ROW_ROR8>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+__device__ __forceinline__ unsigned wave_or(unsigned v)
+{
+    const uint64_t any = __ballot(v != 0);
+    unsigned r = 0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-    return v;
+    for (int b = 0; b < 3; ++b) r |= (__ballot((v >> b) & 1u) != 0) ? (1u << b) : 0u;   // three flag bits exist
+    return any ? r : 0u;
 }
 
 // Single-wave workgroups: this orders LDS traffic between lanes (and stops the compiler from
@@ -612,86 +650,119 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
 }
 
 // =================================================================================================
-// Batch statistics (Sec. 4.4.2): one workgroup, fixed summation order, so results are
-// bit-reproducible from run to run.
+// Batch stage (Sec. 4.4.2 and Alg. 1 step 3) in one launch.  Every workgroup sums the whole batch
+// in the same fixed order (per-thread strided sums, wave butterflies, then the 16 wave partials in
+// index order), so all workgroups hold bit-identical statistics, run to run as well; each then
+// writes the weights of its own slice of tokens.  Workgroup 0 writes the stats struct.
+//   alpha_hat = accepted / proposed;  kappa = alpha_hat / mean_t Z_approx,t
+//   Z_t = kappa Z_approx,t;  w_t = Z_t max(lambda, p(x)/q(x));
+//   rho_t = min(w_t, c1) * min(p_ref(x)/p(x), c2)
 // =================================================================================================
-constexpr int REDUCE_THREADS = 1024;
+constexpr int FINALIZE_THREADS = 1024;
+constexpr int FINALIZE_WAVES = FINALIZE_THREADS / WAVE;
 
-__global__ __launch_bounds__(REDUCE_THREADS) void batch_reduce_kernel(FinalizeArgs A)
+
+__global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs A)
 {
-    __shared__ double sh_z[REDUCE_THREADS], sh_a[REDUCE_THREADS], sh_ze[REDUCE_THREADS];
-    __shared__ long long sh_n[REDUCE_THREADS], sh_acc[REDUCE_THREADS];
-    __shared__ unsigned sh_err[REDUCE_THREADS];
-    const int tid = threadIdx.x;
+    __shared__ double sh_z[FINALIZE_WAVES], sh_a[FINALIZE_WAVES], sh_ze[FINALIZE_WAVES];
+    __shared__ long long sh_n[FINALIZE_WAVES], sh_acc[FINALIZE_WAVES];
+    __shared__ unsigned sh_err[FINALIZE_WAVES];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
     double z = 0.0, a = 0.0, ze = 0.0;
     long long n = 0, nacc = 0;
     unsigned err = 0;
-    for (int64_t t = tid; t < A.T; t += REDUCE_THREADS) {
-        const uint8_t f = A.rowflag[t];
-        if (f == ROW_OK) {
-            n += 1;
-            nacc += A.mask ? (long long)A.mask[t] : 0;
-            z += (double)A.zapprox[t];
-            a += (double)A.accept[t];
-            if (A.zexact) ze += (double)A.zexact[t];
-        } else if (f == ROW_BAD_ID) {
-            err |= JP_DATA_ERR_ID_RANGE;
-        } else if (f == ROW_NONFINITE) {
-            err |= JP_DATA_ERR_NONFINITE;
+    // Inputs of this thread's first token of the weight pass, fetched before the reduction so
+    // their latency overlaps it.
+    const int64_t t0 = (int64_t)blockIdx.x * FINALIZE_THREADS + tid;
+    const bool has0 = t0 < A.T && (A.w || A.rho);
+    const uint8_t f0 = has0 ? A.rowflag[t0] : (uint8_t)ROW_PADDING;
+    const float z0 = has0 ? A.zapprox[t0] : 0.f;
+    const float lr0 = has0 ? A.logratio[t0] : 0.f;
+    const float ref0 = (has0 && A.ref_logprob) ? A.ref_logprob[t0] - A.logp[t0] : 0.f;
+    // Loads of eight rows are issued together (no branch between them) to overlap their latency.
+    constexpr int U = 8;
+    for (int64_t base = tid; base < A.T; base += (int64_t)U * FINALIZE_THREADS) {
+        uint8_t f[U], mk[U];
+        float zv[U], av[U], zev[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t t = base + (int64_t)u * FINALIZE_THREADS;
+            const bool in = t < A.T;
+            f[u] = in ? A.rowflag[t] : (uint8_t)ROW_PADDING;
+            mk[u] = (in && A.mask) ? A.mask[t] : (uint8_t)0;
+            zv[u] = in ? A.zapprox[t] : 0.f;
+            av[u] = in ? A.accept[t] : 0.f;
+            zev[u] = (in && A.zexact) ? A.zexact[t] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (f[u] == ROW_OK) {
+                n += 1;
+                nacc += (long long)mk[u];
+                z += (double)zv[u];
+                a += (double)av[u];
+                ze += (double)zev[u];
+            } else if (f[u] == ROW_BAD_ID) {
+                err |= JP_DATA_ERR_ID_RANGE;
+            } else if (f[u] == ROW_NONFINITE) {
+                err |= JP_DATA_ERR_NONFINITE;
+            }
         }
     }
-    sh_z[tid] = z; sh_a[tid] = a; sh_ze[tid] = ze; sh_n[tid] = n; sh_acc[tid] = nacc; sh_err[tid] = err;
+    z = wave_sum(z); a = wave_sum(a); ze = wave_sum(ze);
+    n = wave_sum_i((int)n); nacc = wave_sum_i((int)nacc);      // per-thread counts are < 2^21
+    err = wave_or(err);
+    if (lane == 0) { sh_z[wv] = z; sh_a[wv] = a; sh_ze[wv] = ze; sh_n[wv] = n; sh_acc[wv] = nacc; sh_err[wv] = err; }
     __syncthreads();
-    for (int o = REDUCE_THREADS / 2; o > 0; o >>= 1) {
-        if (tid < o) {
-            sh_z[tid] += sh_z[tid + o]; sh_a[tid] += sh_a[tid + o]; sh_ze[tid] += sh_ze[tid + o];
-            sh_n[tid] += sh_n[tid + o]; sh_acc[tid] += sh_acc[tid + o]; sh_err[tid] |= sh_err[tid + o];
-        }
-        __syncthreads();
+    z = a = ze = 0.0; n = nacc = 0; err = 0;
+#pragma unroll
+    for (int i = 0; i < FINALIZE_WAVES; ++i) {
+        z += sh_z[i]; a += sh_a[i]; ze += sh_ze[i]; n += sh_n[i]; nacc += sh_acc[i]; err |= sh_err[i];
     }
-    if (tid == 0) {
+    const double nn = (double)n;
+    const double mean_z = z / nn, mean_a = a / nn;
+    const double alpha = A.alpha_expected ? mean_a : (double)nacc / nn;
+    const double kappa = alpha / mean_z;
+    if (blockIdx.x == 0 && tid == 0) {
         jp_obrs_stats st;
-        const double nn = (double)sh_n[0];
-        st.n_valid = sh_n[0];
-        st.n_accept = sh_acc[0];
-        st.mean_z_approx = sh_z[0] / nn;
-        st.mean_accept = sh_a[0] / nn;
-        st.mean_z_exact = A.zexact ? sh_ze[0] / nn : __longlong_as_double(0x7ff8000000000000LL);
-        st.alpha_hat = A.alpha_expected ? st.mean_accept : (double)sh_acc[0] / nn;
-        st.kappa = st.alpha_hat / st.mean_z_approx;
-        st.error_flags = sh_err[0] | (sh_n[0] == 0 ? (unsigned)JP_DATA_ERR_EMPTY : 0u);
+        st.n_valid = n;
+        st.n_accept = nacc;
+        st.alpha_hat = alpha;
+        st.mean_z_approx = mean_z;
+        st.kappa = kappa;
+        st.mean_z_exact = A.zexact ? ze / nn : __longlong_as_double(0x7ff8000000000000LL);
+        st.mean_accept = mean_a;
+        st.error_flags = err | (n == 0 ? (unsigned)JP_DATA_ERR_EMPTY : 0u);
         st.reserved = 0;
         *A.stats = st;
     }
-}
-
-// Weights of Alg. 1 step 3:  Z_t = kappa Z_approx,t;  w_t = Z_t max(lambda, p(x)/q(x));
-// rho_t = min(w_t, c1) * min(p_ref(x)/p(x), c2).
-__global__ __launch_bounds__(256) void weights_kernel(FinalizeArgs A)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= A.T) return;
-    const uint8_t f = A.rowflag[t];
-    float w, rho;
-    if (f == ROW_PADDING) {
-        w = 0.f; rho = 0.f;
-    } else if (f != ROW_OK) {
-        w = rho = __uint_as_float(0x7fc00000u);
-    } else {
-        const double kappa = A.stats->kappa;
-        const double zt = kappa * (double)A.zapprox[t];
-        const double ratio = exp((double)A.logratio[t]);
-        const double lam = (double)A.lambda;
-        const double wd = zt * (lam > ratio ? lam : ratio);
-        double rd = wd < (double)A.c1 ? wd : (double)A.c1;
-        if (A.ref_logprob) {
-            const double rr = exp((double)A.ref_logprob[t] - (double)A.logp[t]);
-            rd *= rr < (double)A.c2 ? rr : (double)A.c2;
+    if (!A.w && !A.rho) return;
+    const double lam = (double)A.lambda;
+    auto weigh = [&](int64_t t, uint8_t f, float zap, float lr, float refdiff) {
+        float w, rho;
+        if (f == ROW_PADDING) {
+            w = 0.f; rho = 0.f;
+        } else if (f != ROW_OK) {
+            w = rho = __uint_as_float(0x7fc00000u);
+        } else {
+            const double zt = kappa * (double)zap;
+            const double ratio = (double)__builtin_amdgcn_exp2f(lr * LOG2E_F);      // p(x)/q(x)
+            const double wd = zt * (lam > ratio ? lam : ratio);
+            double rd = wd < (double)A.c1 ? wd : (double)A.c1;
+            if (A.ref_logprob) {
+                const double rr = (double)__builtin_amdgcn_exp2f(refdiff * LOG2E_F); // p_ref(x)/p(x)
+                rd *= rr < (double)A.c2 ? rr : (double)A.c2;
+            }
+            w = (float)wd; rho = (float)rd;
         }
-        w = (float)wd; rho = (float)rd;
-    }
-    if (A.w) A.w[t] = w;
-    if (A.rho) A.rho[t] = rho;
+        if (A.w) A.w[t] = w;
+        if (A.rho) A.rho[t] = rho;
+    };
+    if (t0 < A.T) weigh(t0, f0, z0, lr0, ref0);
+    const int64_t step = (int64_t)gridDim.x * FINALIZE_THREADS;
+    for (int64_t t = t0 + step; t < A.T; t += step)
+        weigh(t, A.rowflag[t], A.zapprox[t], A.logratio[t],
+              A.ref_logprob ? A.ref_logprob[t] - A.logp[t] : 0.f);
 }
 
 // ---- launchers ------------------------------------------------------------------------------
@@ -728,11 +799,9 @@ hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)
 
 hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL(batch_reduce_kernel, dim3(1), dim3(REDUCE_THREADS), 0, st, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.T <= 0 || (!a.w && !a.rho)) return e;
-    const unsigned blocks = (unsigned)((a.T + 255) / 256);
-    hipLaunchKernelGGL(weights_kernel, dim3(blocks), dim3(256), 0, st, a);
+    int64_t blocks = (a.T + FINALIZE_THREADS - 1) / FINALIZE_THREADS;
+    blocks = blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
+    hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)blocks), dim3(FINALIZE_THREADS), 0, st, a);
     return hipGetLastError();
 }
 
