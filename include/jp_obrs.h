@@ -140,6 +140,30 @@ jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *r
                            const jp_obrs_params *prm, const jp_obrs_outputs *out,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Fused lm_head form of jp_obrs_forward: the logits are not given but computed on the matrix
+ * cores, lq = H_actor x W_actor and lp = H_policy x W_policy (bf16 inputs, fp32 accumulation,
+ * no rounding of the logits), one vocabulary chunk at a time, and consumed by the same row
+ * stage without ever materialising [T, V].  Everything else (Sec. 4.1, 4.4.1, 4.4.2, Alg. 1
+ * steps 2-3) is as in jp_obrs_forward.
+ *   H_actor  [T, d_actor]  bf16 row-major, contiguous, 16-byte aligned; d_actor  % 64 == 0
+ *   W_actor  [d_actor, V]  bf16 row-major, contiguous
+ *   H_policy [T, d_policy], W_policy [d_policy, V] likewise
+ *   vocab_chunk: columns per chunk (rounded up to a multiple of 256); 0 = default (4096)
+ * JP_FLAG_EXACT_Z is not available here (JP_ERR_UNSUPPORTED): the logits are gone after one pass.
+ * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit chunks [T, chunk], the transposed
+ * weight chunks, a per-row record of ~1.6 KB at k <= 64, plus the jp_obrs_forward workspace).
+ */
+size_t jp_obrs_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy,
+                                      int32_t k, int64_t vocab_chunk);
+jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const void *W_actor,
+                                 const void *H_policy, int64_t d_policy, const void *W_policy,
+                                 int64_t T, int64_t V, int64_t vocab_chunk,
+                                 const int32_t *sampled_ids, const float *uniforms,
+                                 const float *ref_logprob, const jp_obrs_params *prm,
+                                 const jp_obrs_outputs *out, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
 const char *jp_status_string(jp_status s);
 
 /* ABI version of this header (bumped on incompatible change). */

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libjp_obrs.so")
-SOURCES = ["jp_obrs_kernels.hip", "jp_obrs_api.hip"]
+SOURCES = ["jp_obrs_kernels.hip", "jp_lmhead_kernels.hip", "jp_obrs_api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

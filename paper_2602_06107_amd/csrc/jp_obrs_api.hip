@@ -140,9 +140,109 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
     return JP_OK;
 }
 
+// ---- fused lm_head path ------------------------------------------------------------------------
+
+struct LmheadPlan {
+    int64_t chunk, npad, nchunks;
+    size_t off_state, off_wt_p, off_wt_a, off_lp, off_lq, bytes;
+    size_t state_stride;
+};
+
+bool plan_lmhead(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_t k, int64_t vocab_chunk,
+                 LmheadPlan &p)
+{
+    if (T < 0 || T > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || k < 1) return false;
+    if (d_actor <= 0 || d_policy <= 0 || d_actor % 64 || d_policy % 64 || d_actor > (1 << 20) || d_policy > (1 << 20)) return false;
+    int64_t c = vocab_chunk > 0 ? vocab_chunk : 4096;
+    c = (c + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
+    const int64_t vpad = (V + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
+    if (c > vpad) c = vpad;
+    p.chunk = c; p.npad = c; p.nchunks = (V + c - 1) / c;
+    p.state_stride = jp::carry_state_bytes(k);
+    size_t off = carve(nullptr, T).bytes;
+    const size_t n = (size_t)(T > 0 ? T : 0);
+    p.off_state = off; off += round_up(n * p.state_stride);
+    p.off_wt_p = off; off += round_up((size_t)c * (size_t)d_policy * 2);
+    p.off_wt_a = off; off += round_up((size_t)c * (size_t)d_actor * 2);
+    p.off_lp = off; off += round_up(n * (size_t)c * 4);
+    p.off_lq = off; off += round_up(n * (size_t)c * 4);
+    p.bytes = off;
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t jp_obrs_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_t k,
+                                      int64_t vocab_chunk)
+{
+    LmheadPlan p;
+    return plan_lmhead(T, V, d_actor, d_policy, k, vocab_chunk, p) ? p.bytes : 0;
+}
+
+jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const void *W_actor,
+                                 const void *H_policy, int64_t d_policy, const void *W_policy,
+                                 int64_t T, int64_t V, int64_t vocab_chunk, const int32_t *sampled_ids,
+                                 const float *uniforms, const float *ref_logprob,
+                                 const jp_obrs_params *prm, const jp_obrs_outputs *out, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (!prm || !out) return JP_ERR_NULL;
+    LmheadPlan pl;
+    if (!plan_lmhead(T, V, d_actor, d_policy, prm->k, vocab_chunk, pl)) {
+        if (prm->k < 1) return JP_ERR_PARAM;
+        return JP_ERR_SHAPE;
+    }
+    jp_status s = check_params(prm, V, true);
+    if (s != JP_OK) return s;
+    if (prm->flags & JP_FLAG_EXACT_Z) return JP_ERR_UNSUPPORTED;   // needs a second pass over logits that are gone
+    if (T > 0 && (!H_actor || !W_actor || !H_policy || !W_policy || !sampled_ids)) return JP_ERR_NULL;
+    if (!aligned16(H_actor) || !aligned16(H_policy) || ((uintptr_t)W_actor & 1) || ((uintptr_t)W_policy & 1)) return JP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < pl.bytes) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (T > 0) {
+        const Workspace w = carve(workspace, T);
+        char *base = (char *)workspace;
+        jp::RowArgs a{};
+        a.actor = base + pl.off_lq; a.policy = base + pl.off_lp;
+        a.T = T; a.stride = pl.npad; a.ids = sampled_ids; a.uni = uniforms;
+        a.lambda = prm->lambda; a.ln_lambda = log((double)prm->lambda); a.k = prm->k;
+        a.accept = out->accept_prob ? out->accept_prob : w.accept;
+        a.logq = out->logq ? out->logq : w.logq;
+        a.logp = out->logp ? out->logp : w.logp;
+        a.logratio = out->logratio ? out->logratio : w.logratio;
+        a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+        a.lse_q = w.lse_q; a.lse_p = w.lse_p;
+        a.mask = out->mask ? out->mask : w.mask;
+        a.rowflag = w.rowflag;
+        a.usize = out->union_size;
+        a.topk_a = out->topk_actor; a.topk_p = out->topk_policy;
+        const bool lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) != 0;
+        a.topk_a_lq = lp ? out->topk_actor_logq : nullptr;
+        a.topk_p_lp = lp ? out->topk_policy_logp : nullptr;
+        a.V_total = V; a.state = (unsigned char *)base + pl.off_state; a.state_stride = (int64_t)pl.state_stride;
+
+        jp::GemmArgs g{};
+        g.A[0] = H_policy; g.Bt[0] = base + pl.off_wt_p; g.C[0] = (float *)(base + pl.off_lp); g.K[0] = (int)d_policy;
+        g.A[1] = H_actor; g.Bt[1] = base + pl.off_wt_a; g.C[1] = (float *)(base + pl.off_lq); g.K[1] = (int)d_actor;
+        g.M = (int)T; g.N = (int)pl.npad; g.nproblems = 2; g.ldc = pl.npad;
+
+        for (int64_t j = 0; j < pl.nchunks; ++j) {
+            const int64_t v0 = j * pl.chunk;
+            const int ncols = (int)((V - v0) < pl.chunk ? (V - v0) : pl.chunk);
+            if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+            if (jp::launch_transpose_chunk(W_actor, V, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+            if (jp::launch_gemm_pair(g, st) != hipSuccess) return JP_ERR_HIP;
+            a.V = ncols; a.id_base = v0; a.carry_in = j > 0; a.carry_out = j + 1 < pl.nchunks;
+            if (jp::launch_rows_carry(a, st) != hipSuccess) return JP_ERR_HIP;
+        }
+    }
+    return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes, st,
+                         uniforms != nullptr);
+}
 
 size_t jp_obrs_workspace_bytes(int64_t T, int64_t V, int32_t k, jp_dtype dt, uint32_t flags)
 {

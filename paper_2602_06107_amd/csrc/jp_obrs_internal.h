@@ -27,7 +27,26 @@ struct RowArgs {
     // optional user outputs
     int32_t *usize, *topk_a, *topk_p;
     float *topk_a_lq, *topk_p_lp;
+    // vocabulary-chunked form only: this launch covers ids [id_base, id_base + V) of V_total
+    int64_t V_total, id_base;
+    int carry_in, carry_out;          // a row record is read before / written after this chunk
+    unsigned char *state;             // [T] records of state_stride bytes (carry_state_bytes(k))
+    int64_t state_stride;
 };
+
+// Row record carried from one vocabulary chunk to the next, followed by the two top-k lists as
+// [2][3][KC] 32-bit words (ids, own logits, the other tensor's logits).
+struct CarryHeader {
+    float M2[2];                      // exponent references (log2 domain) of actor / policy
+    int nl[2];                        // entries in the two lists
+    double S[2];                      // sums of 2^(l log2e - M2)
+    float x_logit[2];                 // logits of the sampled token, once its chunk has passed
+    int have_x, pad;
+    unsigned char reserve[16];
+};
+static_assert(sizeof(CarryHeader) == 64, "carry header is 64 bytes");
+inline int carry_kc(int k) { return k <= 64 ? 64 : (k <= 128 ? 128 : 256); }
+inline size_t carry_state_bytes(int k) { return sizeof(CarryHeader) + (size_t)24 * carry_kc(k); }
 
 struct ZExactArgs {
     const void *actor, *policy;
@@ -49,6 +68,21 @@ struct FinalizeArgs {
 };
 
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
+// Two independent TN GEMMs sharing M, N and ldc (policy head and actor head of one vocabulary chunk).
+struct GemmArgs {
+    const void *A[2];                 // [M, K] bf16
+    const void *Bt[2];                // [N, K] bf16 (N padded to a multiple of 256 with zero rows)
+    float *C[2];                      // [M, ldc] fp32
+    int K[2];
+    int M, N, nproblems;
+    int64_t ldc;
+};
+constexpr int LMHEAD_N_ALIGN = 256;   // GEMM column tile
+
+hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0, int ncols, int npad,
+                                  void *Wt, hipStream_t st);
+hipError_t launch_gemm_pair(const GemmArgs &g, hipStream_t st);
+hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st);   // fp32 logits chunk, carried state
 hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st);
 hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st);
 

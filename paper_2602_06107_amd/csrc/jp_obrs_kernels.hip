@@ -336,7 +336,13 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // =================================================================================================
 // Row kernel: S1-S5 of the hot path for one token position per wavefront.
 // =================================================================================================
-template <class ET, class KT, int KC>
+//
+// CARRY = true is the vocabulary-chunked form used when the logits are produced chunk by chunk
+// (fused lm_head): the row covers ids [id_base, id_base + V) of a vocabulary of V_total tokens,
+// the running row state (exponent reference and sum of both rows, sampled-token logits, the two
+// top-k lists so far with both logits of every entry) is read from / written to a per-row record,
+// and only the launch of the last chunk runs the union / normaliser / acceptance step.
+template <class ET, class KT, int KC, bool CARRY>
 __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
@@ -367,7 +373,14 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
     const float NaN = __uint_as_float(0x7fc00000u);
 
     const int x = A.ids[t];
-    if (x < 0 || x >= V) {                // padding row, or a sampled id outside the vocabulary
+    const int64_t V_total = CARRY ? A.V_total : V;
+    const int64_t id_base = CARRY ? A.id_base : 0;
+    const bool carry_in = CARRY && A.carry_in, carry_out = CARRY && A.carry_out;
+    unsigned char *const state = CARRY ? A.state + (size_t)t * (size_t)A.state_stride : nullptr;
+    CarryHeader *const hdr = (CarryHeader *)state;
+    uint32_t *const st_id0 = (uint32_t *)(state + sizeof(CarryHeader));     // [2][3][KC] words
+    if (x < 0 || x >= V_total) {          // padding row, or a sampled id outside the vocabulary
+        if (carry_out) return;            // reported by the launch of the last chunk
         const bool pad = x < 0;
         const float fill = pad ? 0.f : NaN;
         if (lane == 0) {
@@ -397,6 +410,31 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
 
     Stream<Key> sq{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
     Stream<Key> sp{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
+    int nl_in[2] = {0, 0};                // entries of the carried top-k lists
+    float xq_in = 0.f, xp_in = 0.f;
+    int have_x = 0;
+    if (carry_in) {
+        // Resume the scan: the carried sums go to lane 0, and a full carried list bounds what can
+        // still enter the top-k (its k-th value), exactly as if the sweep had never stopped.
+        sq.M2 = hdr->M2[0]; sp.M2 = hdr->M2[1];
+        if (lane == 0) { sq.s = (float)hdr->S[0]; sp.s = (float)hdr->S[1]; }
+        if (sq.M2 != M2_UNSET) sq.mthr = (sq.M2 + RESCALE_MARGIN2) / LOG2E_F;
+        if (sp.M2 != M2_UNSET) sp.mthr = (sp.M2 + RESCALE_MARGIN2) / LOG2E_F;
+        nl_in[0] = hdr->nl[0]; nl_in[1] = hdr->nl[1];
+        xq_in = hdr->x_logit[0]; xp_in = hdr->x_logit[1]; have_x = hdr->have_x;
+        if (nl_in[0] >= k) {
+            const float vk = __uint_as_float(st_id0[(0 * 3 + 1) * KC + (k - 1)]);
+            const Key b = KT::make(vk, 0xffffffffu);
+            sq.tauk = b > (Key)1 ? b : (Key)1;
+            sq.tauv = threshold_value<KT>(sq.tauk);
+        }
+        if (nl_in[1] >= k) {
+            const float vk = __uint_as_float(st_id0[(1 * 3 + 1) * KC + (k - 1)]);
+            const Key b = KT::make(vk, 0xffffffffu);
+            sp.tauk = b > (Key)1 ? b : (Key)1;
+            sp.tauv = threshold_value<KT>(sp.tauk);
+        }
+    }
 
     auto consume = [&](const float (&fq)[VEC], const float (&fp)[VEC], uint32_t c, bool valid) {
         const float mq = max_of<VEC>(fq), mp = max_of<VEC>(fp);
@@ -453,11 +491,16 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
     }
 
     // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
-    const double lse_q = ((double)sq.M2 + log2_of_sum(wave_sum((double)sq.s))) * LN2_D;
-    const double lse_p = ((double)sp.M2 + log2_of_sum(wave_sum((double)sp.s))) * LN2_D;
+    const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
+    const double lse_q = ((double)sq.M2 + log2_of_sum(Sq)) * LN2_D;
+    const double lse_p = ((double)sp.M2 + log2_of_sum(Sp)) * LN2_D;
     const double ln_lambda = A.ln_lambda;
 
-    const double lq_x = (double)ET::load1(rowq, x), lp_x = (double)ET::load1(rowp, x);
+    // logits of the sampled token (from this chunk if it holds x, else the carried ones)
+    const bool x_here = (int64_t)x >= id_base && (int64_t)x < id_base + V;
+    const float xq = x_here ? ET::load1(rowq, (int64_t)x - id_base) : xq_in;
+    const float xp = x_here ? ET::load1(rowp, (int64_t)x - id_base) : xp_in;
+    const double lq_x = (double)xq, lp_x = (double)xp;
     const double logq_x = lq_x - lse_q, logp_x = lp_x - lse_p;
     const double logratio = logp_x - logq_x;
     // a = min(1, p(x) / (lambda q(x))), taken in the log2 domain
@@ -487,8 +530,22 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         constexpr int i = decltype(tensor_c)::value;
         const char *rowA = i == 0 ? rowq : rowp;
         const char *rowB = i == 0 ? rowp : rowq;
-        const uint32_t thr_ord = (nc[i] >= k) ? KT::ord(uniform_key<Key>(kth[i])) : 0u;
+        uint32_t thr_ord = (nc[i] >= k) ? KT::ord(uniform_key<Key>(kth[i])) : 0u;
         int nS = 0;
+        if (CARRY && nl_in[i] > 0) {
+            // The carried list seeds the candidates; when it is full its k-th value is a second
+            // lower bound of the final k-th value.
+            const uint32_t *cid = st_id0 + (i * 3 + 0) * KC, *ca = cid + KC, *cb = ca + KC;
+            for (int r = lane; r < nl_in[i]; r += WAVE) {
+                s_key[r] = ((uint64_t)ord32(__uint_as_float(ca[r])) << 32) | (uint64_t)(0xffffffffu - cid[r]);
+                s_oth[r] = cb[r];
+            }
+            nS = nl_in[i];
+            if (nl_in[i] >= k) {
+                const uint32_t ok = ord32(__uint_as_float(ca[k - 1]));
+                thr_ord = ok > thr_ord ? ok : thr_ord;
+            }
+        }
 
         // Rank the nS buffered candidates; the best min(nS, k) go to list i in rank order.
         auto rank_slots = [&](auto nslots_c) {
@@ -550,9 +607,10 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
                     nS = keep;
                     lds_sync();
                 }
-                const int64_t id = (int64_t)c * VEC + j;
+                const int64_t lid = (int64_t)c * VEC + j;
+                const int64_t id = id_base + lid;
                 const uint32_t o = ord32(fa[j]);
-                const bool ok = has && id < V && o >= thr_ord;
+                const bool ok = has && lid < V && o >= thr_ord;
                 const uint64_t m = __ballot(ok);
                 if (ok) {
                     const int pos = nS + lane_prefix(m);
@@ -567,6 +625,26 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
     };
     expand(std::integral_constant<int, 0>{});
     expand(std::integral_constant<int, 1>{});
+
+    if (carry_out) {                      // hand the row state to the launch of the next chunk
+        if (lane == 0) {
+            hdr->M2[0] = sq.M2; hdr->M2[1] = sp.M2;
+            hdr->S[0] = Sq; hdr->S[1] = Sp;
+            hdr->nl[0] = nl[0]; hdr->nl[1] = nl[1];
+            hdr->x_logit[0] = xq; hdr->x_logit[1] = xp;
+            hdr->have_x = (have_x || x_here) ? 1 : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            uint32_t *cid = st_id0 + (i * 3 + 0) * KC, *ca = cid + KC, *cb = ca + KC;
+            for (int r = lane; r < nl[i]; r += WAVE) {
+                cid[r] = l_id[i][r];
+                ca[r] = __float_as_uint(l_a[i][r]);
+                cb[r] = __float_as_uint(l_b[i][r]);
+            }
+        }
+        return;
+    }
 
     // ---- V_k = union of the two lists; Z_approx = sum over V_k of min(q, p/lambda) -------------
     // In the log domain min(q, p/lambda) = exp(min(lq - LSEq, lp - LSEp - ln lambda)).
@@ -771,9 +849,19 @@ template <class ET, class KT>
 static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64>), grid, block, 0, st, a);
-    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_kernel<ET, KT, 256>), grid, block, 0, st, a);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

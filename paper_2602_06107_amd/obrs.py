@@ -24,6 +24,7 @@ JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
  JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
 
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
+           "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -66,6 +67,13 @@ _lib.jp_obrs_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_
 _lib.jp_obrs_finalize.restype = C.c_int
 _lib.jp_obrs_finalize.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(Params),
                                   C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_lmhead_workspace_bytes.restype = C.c_size_t
+_lib.jp_obrs_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int64]
+_lib.jp_obrs_forward_lmhead.restype = C.c_int
+_lib.jp_obrs_forward_lmhead.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                        C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(Params), C.POINTER(Outputs), C.c_void_p, C.c_size_t,
+                                        C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -125,7 +133,13 @@ class Buffers:
         return Stats.from_buffer_copy(raw)
 
 
-def alloc_buffers(T: int, V: int, k: int, dt: int, flags: int, device, want=None) -> Buffers:
+def jp_obrs_lmhead_workspace_bytes(T: int, V: int, d_actor: int, d_policy: int, k: int,
+                                   vocab_chunk: int = 0) -> int:
+    return _lib.jp_obrs_lmhead_workspace_bytes(T, V, d_actor, d_policy, k, vocab_chunk)
+
+
+def alloc_buffers(T: int, V: int, k: int, dt: int, flags: int, device, want=None,
+                  workspace_bytes: Optional[int] = None) -> Buffers:
     """Allocate outputs + workspace with torch.  ``want``: iterable of output names (default all)."""
     names = set(_OUT_FIELDS if want is None else want)
     f32 = dict(dtype=torch.float32, device=device)
@@ -149,7 +163,7 @@ def alloc_buffers(T: int, V: int, k: int, dt: int, flags: int, device, want=None
     if "stats" in names:
         t["stats"] = torch.zeros(C.sizeof(Stats), dtype=torch.uint8, device=device)
     out = Outputs(**{n: (t[n].data_ptr() if n in t else None) for n in _OUT_FIELDS})
-    nbytes = jp_obrs_workspace_bytes(T, V, k, dt, flags)
+    nbytes = jp_obrs_workspace_bytes(T, V, k, dt, flags) if workspace_bytes is None else workspace_bytes
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
     return Buffers(out, t, ws)
 
@@ -189,6 +203,26 @@ def jp_obrs_finalize(T, sampled_ids, ref_logprob, lam, k, c1, c2, flags, buf: Bu
     prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
     st = _lib.jp_obrs_finalize(int(T), _p(sampled_ids), _p(ref_logprob), C.byref(prm), C.byref(buf.out),
                                _p(buf.workspace), buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_forward_lmhead(H_actor, W_actor, H_policy, W_policy, sampled_ids, uniforms, ref_logprob,
+                           lam, k, c1, c2, flags, buf: Buffers, vocab_chunk: int = 0, stream=None) -> None:
+    """Fused lm_head form: logits = H x W on the matrix cores, chunk by chunk over the vocabulary."""
+    for t in (H_actor, W_actor, H_policy, W_policy):
+        if t.dtype != torch.bfloat16 or t.dim() != 2 or not t.is_contiguous():
+            raise ValueError("hidden states and weights must be contiguous 2-D bfloat16 tensors")
+    T, d_a = H_actor.shape
+    d_p = H_policy.shape[1]
+    V = W_actor.shape[1]
+    if H_policy.shape[0] != T or W_actor.shape[0] != d_a or tuple(W_policy.shape) != (d_p, V):
+        raise ValueError("shape mismatch between hidden states and weights")
+    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    st = _lib.jp_obrs_forward_lmhead(_p(H_actor), d_a, _p(W_actor), _p(H_policy), d_p, _p(W_policy), T, V,
+                                     int(vocab_chunk), _p(sampled_ids), _p(uniforms), _p(ref_logprob),
+                                     C.byref(prm), C.byref(buf.out), _p(buf.workspace),
+                                     buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 

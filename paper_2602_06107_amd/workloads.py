@@ -164,3 +164,72 @@ def bf16_bits_to_float64(bits: np.ndarray) -> np.ndarray:
 def logits_to_float64(t: torch.Tensor) -> np.ndarray:
     a = logits_to_numpy(t)
     return bf16_bits_to_float64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+# ---- fused lm_head form: hidden states and vocabulary projections instead of logits --------------
+
+@dataclass
+class LmHeadWorkload:
+    name: str
+    H_actor: torch.Tensor        # [T, d_actor]  bf16
+    W_actor: torch.Tensor        # [d_actor, V]  bf16
+    H_policy: torch.Tensor       # [T, d_policy] bf16
+    W_policy: torch.Tensor       # [d_policy, V] bf16
+    sampled_ids: torch.Tensor    # [T] int32
+    uniforms: torch.Tensor       # [T] fp32
+    lam: float = 1.0
+    k: int = 64
+    c1: float = 3.0
+    c2: float = 3.0
+    ref_logprob: Optional[torch.Tensor] = None
+
+    @property
+    def T(self) -> int:
+        return self.H_actor.shape[0]
+
+    @property
+    def V(self) -> int:
+        return self.W_actor.shape[1]
+
+    def with_params(self, **kw) -> "LmHeadWorkload":
+        return replace(self, **kw)
+
+
+def lm_head(T: int = 16384, V: int = QWEN3_VOCAB, d_actor: int = 2048, d_policy: int = 4096,
+            device="cuda", seed: int = BASE_SEED + 4, k: int = 64, name: str = "lm_head") -> LmHeadWorkload:
+    """Hidden states N(0,1), projections N(0, 1/d), all bf16; the sampled token is drawn from
+    softmax(H_actor W_actor) by Gumbel-max over vocabulary blocks (fp32 matmul of the harness)."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+
+    def normal(shape, sigma):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * sigma).to(torch.bfloat16)
+
+    Ha, Wa = normal((T, d_actor), 1.0), normal((d_actor, V), d_actor ** -0.5)
+    Hp, Wp = normal((T, d_policy), 1.0), normal((d_policy, V), d_policy ** -0.5)
+    best = torch.full((T,), float("-inf"), device=dev)
+    ids = torch.zeros(T, dtype=torch.int64, device=dev)
+    blk = 8192
+    Haf = Ha.float()
+    for v0 in range(0, V, blk):
+        logits = Haf @ Wa[:, v0:v0 + blk].float()
+        u = torch.rand(logits.shape, generator=gen, device=dev, dtype=torch.float32)
+        u.clamp_(min=1e-20, max=1.0 - 1e-7)
+        logits.add_(-torch.log(-torch.log(u)))
+        m, a = logits.max(dim=1)
+        upd = m > best
+        best = torch.where(upd, m, best)
+        ids = torch.where(upd, a + v0, ids)
+    uni = torch.rand(T, generator=gen, device=dev, dtype=torch.float32)
+    return LmHeadWorkload(name, Ha, Wa, Hp, Wp, ids.to(torch.int32), uni, k=k)
+
+
+def lm_head_logits_float64(w: LmHeadWorkload, rows) -> tuple:
+    """Exact-input float64 logits of the given rows: (actor [n, V], policy [n, V]) as numpy arrays."""
+    r = torch.as_tensor(rows, device=w.H_actor.device)
+    Ha = w.H_actor[r].cpu().double().numpy()
+    Hp = w.H_policy[r].cpu().double().numpy()
+    Wa = w.W_actor.cpu().double().numpy()
+    Wp = w.W_policy.cpu().double().numpy()
+    return Ha @ Wa, Hp @ Wp

@@ -1,0 +1,125 @@
+"""GPU parity of the fused lm_head form: logits come from the matrix cores (bf16 x bf16 -> fp32)
+one vocabulary chunk at a time; the oracle forms them in float64 from the same bf16 bits.
+
+Because the two sides round the logits differently (~1e-5), a top-k list may differ from the
+oracle's where two logits are nearly tied: an id list is accepted if, rank by rank, the float64
+logit of the GPU's id is within 1e-4 max(1, |l|) of the oracle's; Z_approx is then compared on the
+set the GPU chose.  Floats: the bf16-input bar (rel 1e-3, absolute for log-domain values)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from oracle import obrs_oracle as orc
+    from paper_2602_06107_amd import obrs
+    from paper_2602_06107_amd import workloads as wl
+    import parity_util as pu
+
+DEV = "cuda"
+TOL = 1e-3
+TIE = 1e-4
+
+
+def _run(w, flags=0, vocab_chunk=0):
+    T, V = w.T, w.V
+    nbytes = obrs.jp_obrs_lmhead_workspace_bytes(T, V, w.H_actor.shape[1], w.H_policy.shape[1], w.k, vocab_chunk)
+    assert nbytes > 0
+    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, flags, DEV, workspace_bytes=nbytes)
+    obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids, w.uniforms,
+                                w.ref_logprob, w.lam, w.k, w.c1, w.c2, flags, buf, vocab_chunk)
+    torch.cuda.synchronize()
+    return buf
+
+
+def _check(w, buf, rows, flags=0, batch=True):
+    lq, lp = wl.lm_head_logits_float64(w, rows)
+    x = w.sampled_ids.cpu().numpy()[rows]
+    u = w.uniforms.cpu().numpy()[rows]
+    R = orc.rows(lq, lp, x, u, w.lam, w.k)
+    o = R.out
+    g = {n: t.cpu().numpy()[rows] for n, t in buf.tensors.items() if n != "stats"}
+    pu._close(g["logq"], o["logq_x"], 0.0, "log q(x)", abs_tol=TOL)
+    pu._close(g["logp"], o["logp_x"], 0.0, "log p(x)", abs_tol=TOL)
+    pu._close(g["logratio"], o["logratio"], 0.0, "log ratio", abs_tol=TOL)
+    pu._close(g["accept_prob"], o["accept"], TOL, "a(x)")
+    n_swapped = 0
+    for i in range(len(rows)):
+        for got, want, l in ((g["topk_actor"][i], R.topk_q[i], lq[i]), (g["topk_policy"][i], R.topk_p[i], lp[i])):
+            assert len(set(got.tolist())) == w.k and got.min() >= 0 and got.max() < w.V
+            if not np.array_equal(got, want):
+                n_swapped += 1
+                d = np.abs(l[got] - l[want])
+                assert np.all(d <= TIE * np.maximum(1.0, np.abs(l[want]))), (rows[i], d.max())
+        logq = lq[i] - o["lse_q"][i]
+        logp = lp[i] - o["lse_p"][i]
+        U = np.array(sorted(set(g["topk_actor"][i].tolist()) | set(g["topk_policy"][i].tolist())))
+        assert g["union_size"][i] == len(U)
+        z = np.minimum(np.exp(logq[U]), np.exp(logp[U]) / w.lam).sum()
+        pu._close(g["z_approx"][i], z, TOL, "Z_approx on the GPU's set")
+        if np.array_equal(g["topk_actor"][i], R.topk_q[i]) and np.array_equal(g["topk_policy"][i], R.topk_p[i]):
+            pu._close(g["z_approx"][i], o["z_approx"][i], TOL, "Z_approx")
+        if flags & obrs.JP_FLAG_TOPK_LOGPROBS:
+            pu._close(g["topk_actor_logq"][i], logq[g["topk_actor"][i]], 0.0, "top-k log q", abs_tol=TOL)
+            pu._close(g["topk_policy_logp"][i], logp[g["topk_policy"][i]], 0.0, "top-k log p", abs_tol=TOL)
+    band = np.abs(u - o["accept"]) <= TOL * np.maximum(o["accept"], 1e-30)
+    np.testing.assert_array_equal(g["mask"][~band], o["mask"][~band])
+    if batch:      # rows == all rows
+        mask = g["mask"].astype(np.int32)
+        rows_for_batch = o.copy()
+        rows_for_batch["z_approx"] = g["z_approx"]          # GPU's sets where near-ties swapped
+        b, w_want, rho_want = orc.batch(rows_for_batch, mask, w.lam, w.c1, w.c2,
+                                        None if w.ref_logprob is None else w.ref_logprob.cpu().numpy().astype(np.float64))
+        st = buf.stats()
+        assert st.n_valid == b.n_valid and st.n_accept == b.n_accept and st.error_flags == 0
+        pu._close(st.kappa, b.kappa, TOL, "kappa")
+        pu._close(g["w_obrs"], w_want, 2 * TOL, "w_OBRS")
+        pu._close(g["rho"], rho_want, 2 * TOL, "rho")
+    return n_swapped
+
+
+@pytest.mark.parametrize("T,V,da,dp,k,chunk", [
+    (48, 3000, 128, 192, 16, 512),       # several chunks, ragged last chunk, ragged row tile
+    (300, 1000, 64, 64, 8, 256),         # more than one row tile
+    (17, 700, 64, 128, 64, 0),           # single chunk
+    (33, 5000, 256, 128, 100, 1024),     # k class 128
+])
+def test_lmhead_small_shapes(T, V, da, dp, k, chunk):
+    print(f"lm_head T={T} V={V} d=({da},{dp}) k={k} chunk={chunk}", flush=True)
+    w = wl.lm_head(T, V, da, dp, DEV, seed=100 + T, k=k).with_params(lam=1.2)
+    w.ref_logprob = -torch.rand(T, device=DEV)
+    buf = _run(w, obrs.JP_FLAG_TOPK_LOGPROBS, chunk)
+    _check(w, buf, np.arange(T), obrs.JP_FLAG_TOPK_LOGPROBS)
+
+
+def test_lmhead_matches_materialised_path():
+    """Same inputs through jp_obrs_forward on fp32 logits made by torch: ids agree except at
+    near-ties and the scalars agree to the bf16 bar."""
+    print("lm_head vs materialised fp32 logits, T=64 V=20000", flush=True)
+    w = wl.lm_head(64, 20000, 128, 256, DEV, seed=7, k=32)
+    buf = _run(w, 0, 2048)
+    la = (w.H_actor.float() @ w.W_actor.float()).contiguous()
+    lp = (w.H_policy.float() @ w.W_policy.float()).contiguous()
+    wm = wl.Workload("mat", la, lp, w.sampled_ids, w.uniforms, lam=w.lam, k=w.k)
+    bm = obrs.run_workload(wm)
+    torch.cuda.synchronize()
+    same = (buf.topk_actor == bm.topk_actor).all(dim=1) & (buf.topk_policy == bm.topk_policy).all(dim=1)
+    assert same.float().mean() > 0.9
+    np.testing.assert_allclose(buf.z_approx[same].cpu().numpy(), bm.z_approx[same].cpu().numpy(), rtol=1e-4)
+    np.testing.assert_allclose(buf.logratio.cpu().numpy(), bm.logratio.cpu().numpy(), atol=1e-4)
+
+
+def test_lmhead_rejects_bad_arguments():
+    w = wl.lm_head(8, 512, 64, 64, DEV, seed=3, k=4)
+    buf = obrs.alloc_buffers(8, 512, 4, obrs.JP_F32, 0, DEV, workspace_bytes=obrs.jp_obrs_lmhead_workspace_bytes(8, 512, 64, 64, 4, 0))
+    with pytest.raises(obrs.JpError) as e:
+        obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids, w.uniforms,
+                                    None, 1.0, 4, 3.0, 3.0, obrs.JP_FLAG_EXACT_Z, buf)
+    assert e.value.status == obrs.JP_ERR_UNSUPPORTED
+    assert obrs.jp_obrs_lmhead_workspace_bytes(8, 512, 60, 64, 4, 0) == 0      # d not a multiple of 64
+    small = obrs.alloc_buffers(8, 512, 4, obrs.JP_F32, 0, DEV)
+    with pytest.raises(obrs.JpError) as e:
+        obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids, w.uniforms,
+                                    None, 1.0, 4, 3.0, 3.0, 0, small)
+    assert e.value.status == obrs.JP_ERR_WORKSPACE
