@@ -40,17 +40,60 @@ def algorithmic_bytes_per_token(V: int, k: int, esz: int) -> int:
     return reads + writes
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def bench_lm_head(args, torch, obrs, wl, dev):
+    """Context figure for the fused lm_head form (T=16384, d=2048/4096, V=151936, k=64): a step is
+    one jp_obrs_forward_lmhead call; the roofline is the dense bf16 MFMA peak against the flops of
+    the two projections over the whole call (transposes and row kernels included)."""
+    T = args.tokens if args.tokens > 0 else 16384
+    w = wl.lm_head(T=T, device=dev, k=args.k if args.k > 0 else 64).with_params(lam=args.lam)
+    V, da, dp = w.V, w.H_actor.shape[1], w.H_policy.shape[1]
+    nbytes = obrs.jp_obrs_lmhead_workspace_bytes(T, V, da, dp, w.k, args.vocab_chunk)
+    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, 0, dev, workspace_bytes=nbytes)
+
+    def step():
+        obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids,
+                                    w.uniforms, None, w.lam, w.k, w.c1, w.c2, 0, buf, args.vocab_chunk)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    st = buf.stats()
+    flops = 2.0 * T * V * (da + dp)
+    tflops = flops * args.steps / wall / 1e12
+    print(json.dumps({
+        "metric": "OBRS tokens/sec, fused lm_head form (context, not the headline metric)",
+        "value": T * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
+        "config": {"workload": "lm_head: T=%d, d_actor=%d, d_policy=%d, V=%d, k=%d, lambda=%g, chunk=%d"
+                               % (T, da, dp, V, w.k, w.lam, args.vocab_chunk or 4096),
+                   "kappa": st.kappa, "alpha_hat": st.alpha_hat},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "whole call (gemm_tn_kernel dominates)", "flops": flops},
+        "cpu_baseline": None}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["rollout", "training", "long"], default="rollout",
+    ap.add_argument("--workload", choices=["rollout", "training", "long", "lm_head"], default="rollout",
                     help="rollout (T=8192, k=64) is the configuration the metric is quoted on; the "
                          "others are for context")
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--k", type=int, default=0, help="override k of the workload")
     ap.add_argument("--lam", type=float, default=1.0)
+    ap.add_argument("--vocab-chunk", type=int, default=0, help="lm_head workload: columns per chunk")
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
                          "a kernel of known HBM traffic that scales rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -71,6 +114,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload == "lm_head":
+        return bench_lm_head(args, torch, obrs, wl, dev)
     make = {"rollout": wl.rollout, "training": wl.training, "long": wl.long_response}[args.workload]
     w = make(dev, T=args.tokens) if args.tokens > 0 else make(dev)
     w = w.with_params(lam=args.lam, k=args.k if args.k > 0 else w.k)

@@ -140,19 +140,27 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
         const int stage = kt & 1;
         if (kt + 1 < nk) gload(kt + 1);
         const unsigned char *ta = lds + stage * 2 * TILE_BYTES, *tb = ta + TILE_BYTES;
-#pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            bf16x8 fa[4], fb[4];
+        // Fragments of k-step s+1 are fetched from LDS before the 16 MFMAs of step s are issued,
+        // so their latency hides behind the matrix pipe.
+        bf16x8 fa[2][4], fb[2][4];
+        auto lfrag = [&](int s, int b) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                fa[i] = *(const bf16x8 *)(ta + tile_offset(wm * 128 + i * 32 + li, 2 * s + lg));
-                fb[i] = *(const bf16x8 *)(tb + tile_offset(wn * 128 + i * 32 + li, 2 * s + lg));
+                fa[b][i] = *(const bf16x8 *)(ta + tile_offset(wm * 128 + i * 32 + li, 2 * s + lg));
+                fb[b][i] = *(const bf16x8 *)(tb + tile_offset(wn * 128 + i * 32 + li, 2 * s + lg));
             }
+        };
+        lfrag(0, 0);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            if (s + 1 < BK / 16) lfrag(s + 1, (s + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (kt + 1 < nk) lstore(stage ^ 1);
         __syncthreads();

@@ -123,3 +123,20 @@ def test_lmhead_rejects_bad_arguments():
         obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids, w.uniforms,
                                     None, 1.0, 4, 3.0, 3.0, 0, small)
     assert e.value.status == obrs.JP_ERR_WORKSPACE
+
+
+def test_lmhead_full_size():
+    """T=16384, d=2048/4096, V=151936, k=64: sampled rows against the oracle, batch statistics
+    through their defining relations on the per-row outputs."""
+    print("lm_head full size: T=16384 V=151936 d=(2048,4096) k=64", flush=True)
+    w = wl.lm_head(device=DEV)
+    buf = _run(w, 0, 0)
+    rows = np.array([0, 1, 4099, 8191, 12000, 16382, 16383])
+    n_swapped = _check(w, buf, rows, 0, batch=False)
+    print(f"  lists with a near-tie swap among {2 * len(rows)}: {n_swapped}", flush=True)
+    st = buf.stats()
+    g = {n: buf.tensors[n].cpu().numpy().astype(np.float64) for n in ("accept_prob", "z_approx", "logratio", "w_obrs", "mask")}
+    assert st.error_flags == 0 and st.n_valid == w.T and st.n_accept == int(g["mask"].sum())
+    assert st.kappa == pytest.approx(g["mask"].mean() / g["z_approx"].mean(), rel=1e-9)
+    np.testing.assert_allclose(g["w_obrs"], st.kappa * g["z_approx"] * np.maximum(w.lam, np.exp(g["logratio"])), rtol=1e-5)
+    print(f"  alpha_hat={st.alpha_hat:.4f} mean Z_approx={st.mean_z_approx:.4f} kappa={st.kappa:.4f}", flush=True)
