@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "jp_obrs_internal.h"
 
 namespace jp {
@@ -25,9 +27,11 @@ constexpr int GEMM_THREADS = 256;
 constexpr int TILE_BYTES = BM * BK * 2;            // 32 KB per operand tile
 constexpr int ROW_BYTES = BK * 2;                  // 128 B: eight 16-byte pieces per tile row
 
-// Piece p (0..7) of tile row r is stored at piece p ^ (r & 7): eight consecutive rows then cover
-// all 32 banks once, for the 16-byte fragment reads as well as for the staging writes.
-__device__ __forceinline__ int tile_offset(int row, int piece) { return row * ROW_BYTES + ((piece ^ (row & 7)) << 4); }
+// Piece p (0..7) of tile row r is stored at piece p ^ ((r >> 1) & 7).  The LDS serves 256 bytes
+// (64 banks) per cycle, i.e. 16 lanes of a 16-byte access: consecutive rows alternate between the
+// two 128-byte halves of the bank space, and rows of equal parity get distinct pieces, so the 16
+// rows a fragment read touches per cycle are conflict-free (measured with SQ_LDS_BANK_CONFLICT).
+__device__ __forceinline__ int tile_offset(int row, int piece) { return row * ROW_BYTES + ((piece ^ ((row >> 1) & 7)) << 4); }
 
 }  // namespace
 
@@ -97,14 +101,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
     // staging: thread owns piece (tid & 7) of rows (tid >> 3) + 32 i, i < 8, of both tiles
     const int sp = tid & 7, sr = tid >> 3;
     const int64_t ldk = (int64_t)K * 2;                      // bytes per row of A / Bt
-    const unsigned char *ga[8], *gb[8];
+    const unsigned char *abase = A + (int64_t)tile_m * BM * ldk;     // wave-uniform tile origins
+    const unsigned char *bbase = B + (int64_t)tile_n * BN * ldk;
+    uint32_t oa[8], ob[8];                                   // byte offsets inside the tile's rows
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        int ra = tile_m * BM + sr + 32 * i;
-        ra = ra < M ? ra : M - 1;                            // rows past M repeat the last row (never stored)
-        const int rb = tile_n * BN + sr + 32 * i;
-        ga[i] = A + (int64_t)ra * ldk + sp * 16;
-        gb[i] = B + (int64_t)rb * ldk + sp * 16;
+        int ra = sr + 32 * i;
+        const int last = M - 1 - tile_m * BM;                // rows past M repeat the last row (never stored)
+        ra = ra < last ? ra : last;
+        oa[i] = (uint32_t)ra * (uint32_t)ldk + sp * 16;
+        ob[i] = (uint32_t)(sr + 32 * i) * (uint32_t)ldk + sp * 16;
     }
 
     f32x16 acc[4][4];
@@ -115,54 +121,70 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 ra_[8], rb_[8];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            ra_[i] = *(gvec_ptr)(uintptr_t)(ga[i] + (int64_t)kt * ROW_BYTES);
-            rb_[i] = *(gvec_ptr)(uintptr_t)(gb[i] + (int64_t)kt * ROW_BYTES);
-        }
-    };
-    auto lstore = [&](int stage) {
-        unsigned char *ta = lds + stage * 2 * TILE_BYTES, *tb = ta + TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *(u32x4 *)(ta + tile_offset(sr + 32 * i, sp)) = ra_[i];
-            *(u32x4 *)(tb + tile_offset(sr + 32 * i, sp)) = rb_[i];
-        }
-    };
-
+    // Global -> register -> LDS staging with the memory instructions spread between the MFMAs:
+    // during k-tile kt the 16 ds_writes that put tile kt+1 (already in registers) into the other
+    // LDS stage ride behind the first 32 MFMAs, and the 16 global loads of tile kt+2 ride behind
+    // the last 32, so neither the vector-memory nor the LDS queue ever stalls the matrix pipe and
+    // every load has about one and a half k-tiles (~1.3 us) to arrive.
+    u32x4 stg[16];                                           // pieces 0-7: A rows, 8-15: Bt rows
     const int nk = K / BK;
-    gload(0);
-    lstore(0);
+    const uint32_t st_off = (uint32_t)tile_offset(sr, sp);   // rows 32 apart share their swizzle
+    auto gload_piece = [&](int kt, int p) __attribute__((always_inline)) {
+        const int kc = kt < nk ? kt : nk - 1;                // past the end: a harmless repeat
+        stg[p] = p < 8 ? *(gvec_ptr)(uintptr_t)(abase + oa[p] + kc * ROW_BYTES)
+                       : *(gvec_ptr)(uintptr_t)(bbase + ob[p - 8] + kc * ROW_BYTES);
+    };
+    auto lstore_piece = [&](int stage, int p) __attribute__((always_inline)) {
+        unsigned char *t = lds + stage * 2 * TILE_BYTES + st_off + (p < 8 ? 0 : TILE_BYTES) + (p & 7) * 32 * ROW_BYTES;
+        *(u32x4 *)t = stg[p];
+    };
+    uint32_t fa_off[BK / 16], fb_off[BK / 16];               // fragment addresses of the 4 k-steps
+#pragma unroll
+    for (int s2 = 0; s2 < BK / 16; ++s2) {
+        fa_off[s2] = (uint32_t)tile_offset(wm * 128 + li, 2 * s2 + lg);
+        fb_off[s2] = (uint32_t)(TILE_BYTES + tile_offset(wn * 128 + li, 2 * s2 + lg));
+    }
+
+#pragma unroll
+    for (int p = 0; p < 16; ++p) gload_piece(0, p);
+#pragma unroll
+    for (int p = 0; p < 16; ++p) lstore_piece(0, p);
+#pragma unroll
+    for (int p = 0; p < 16; ++p) gload_piece(1, p);
     __syncthreads();
+
     for (int kt = 0; kt < nk; ++kt) {
         const int stage = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
-        const unsigned char *ta = lds + stage * 2 * TILE_BYTES, *tb = ta + TILE_BYTES;
-        // Fragments of k-step s+1 are fetched from LDS before the 16 MFMAs of step s are issued,
-        // so their latency hides behind the matrix pipe.
+        const unsigned char *ts = lds + stage * 2 * TILE_BYTES;
         bf16x8 fa[2][4], fb[2][4];
-        auto lfrag = [&](int s, int b) {
+        auto lfrag = [&](int s2, int b2) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                fa[b][i] = *(const bf16x8 *)(ta + tile_offset(wm * 128 + i * 32 + li, 2 * s + lg));
-                fb[b][i] = *(const bf16x8 *)(tb + tile_offset(wn * 128 + i * 32 + li, 2 * s + lg));
+                fa[b2][i] = *(const bf16x8 *)(ts + fa_off[s2] + i * 32 * ROW_BYTES);
+                fb[b2][i] = *(const bf16x8 *)(ts + fb_off[s2] + i * 32 * ROW_BYTES);
             }
         };
         lfrag(0, 0);
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            if (s + 1 < BK / 16) lfrag(s + 1, (s + 1) & 1);
+        for (int s2 = 0; s2 < BK / 16; ++s2) {
+            if (s2 + 1 < BK / 16) lfrag(s2 + 1, (s2 + 1) & 1);   // fragments one k-step ahead
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s2 & 1][i], fb[s2 & 1][j], acc[i][j], 0, 0, 0);
+                const int r = s2 * 4 + i;                    // 16 MFMA rows per k-tile
+                if (r < 8) {
+                    lstore_piece(stage ^ 1, 2 * r);
+                    lstore_piece(stage ^ 1, 2 * r + 1);
+                } else {
+                    gload_piece(kt + 2, 2 * (r - 8));
+                    gload_piece(kt + 2, 2 * (r - 8) + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (kt + 1 < nk) lstore(stage ^ 1);
         __syncthreads();
     }
 
