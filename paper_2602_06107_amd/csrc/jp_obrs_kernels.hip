@@ -576,9 +576,14 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         auto rank_to_list = [&]() {
             if (lane == 0) s_key[nS] = 0;
             lds_sync();
-            if (nS <= WAVE) rank_slots(std::integral_constant<int, 1>{});
-            else if (nS <= 2 * WAVE) rank_slots(std::integral_constant<int, 2>{});
-            else rank_slots(std::integral_constant<int, ES>{});
+            // one instantiation per number of 64-entry slots actually in use
+            auto pick = [&](auto self, auto n_c) -> void {
+                constexpr int N = decltype(n_c)::value;
+                if constexpr (N >= ES) rank_slots(std::integral_constant<int, ES>{});
+                else if (nS <= N * WAVE) rank_slots(n_c);
+                else self(self, std::integral_constant<int, N + 1>{});
+            };
+            pick(pick, std::integral_constant<int, 1>{});
             lds_sync();
         };
 
@@ -658,10 +663,34 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         if (A.topk_a) A.topk_a[t * k + r] = (int32_t)l_id[0][r];
         if (A.topk_a_lq) A.topk_a_lq[t * k + r] = finite_row ? (float)dq : NaN;
     }
+    // Membership of the policy list's ids in the actor list through a small open-addressing hash
+    // table (load factor <= 1/4) in the LDS pool, which is free by now.
+    constexpr int HT = 4 * KC;
+    static_assert(HT * 4 <= POOL_BYTES, "hash table must fit the pool");
+    uint32_t *const tab = (uint32_t *)pool;
+    lds_sync();
+    for (int e = lane; e < HT; e += WAVE) tab[e] = 0xffffffffu;
+    lds_sync();
+    for (int r = lane; r < nl[0]; r += WAVE) {
+        const uint32_t id = l_id[0][r];
+        uint32_t slot = (id * 2654435761u) >> 7 & (HT - 1);
+        for (int tries = 0; tries < HT; ++tries) {
+            const uint32_t old = atomicCAS(&tab[slot], 0xffffffffu, id);
+            if (old == 0xffffffffu || old == id) break;
+            slot = (slot + 1) & (HT - 1);
+        }
+    }
+    lds_sync();
     for (int r = lane; r < nl[1]; r += WAVE) {
         const uint32_t id = l_id[1][r];
         bool dup = false;
-        for (int j = 0; j < nl[0]; ++j) dup |= (l_id[0][j] == id);
+        uint32_t slot = (id * 2654435761u) >> 7 & (HT - 1);
+        for (int tries = 0; tries < HT; ++tries) {
+            const uint32_t v = tab[slot];
+            if (v == id) { dup = true; break; }
+            if (v == 0xffffffffu) break;
+            slot = (slot + 1) & (HT - 1);
+        }
         const double dp0 = (double)l_a[1][r] - lse_p;
         const double dq = (double)l_b[1][r] - lse_q;
         const double dp = dp0 - ln_lambda;
