@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--k", type=int, default=0, help="override k of the workload")
     ap.add_argument("--lam", type=float, default=1.0)
+    ap.add_argument("--flags", type=int, default=0,
+                    help="JP_FLAG_* bits for the timed calls (default 0: the hot path as quoted; "
+                         "8 adds the per-token distillation KL to the same sweep)")
     ap.add_argument("--vocab-chunk", type=int, default=0, help="lm_head workload: columns per chunk")
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
@@ -121,12 +124,12 @@ def main():
     w = w.with_params(lam=args.lam, k=args.k if args.k > 0 else w.k)
     T, V = w.T, w.V
     esz = w.actor.element_size()
-    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, 0, dev)
+    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, args.flags, dev)
     torch.cuda.synchronize()
 
     def step():
         obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, None, w.lam, w.k, w.c1,
-                             w.c2, 0, buf)
+                             w.c2, args.flags, buf)
 
     for _ in range(args.warmup):
         step()
@@ -145,7 +148,7 @@ def main():
            for _ in range(args.steps)]
     for a, b in evs:
         a.record()
-        obrs.jp_obrs_rows(w.actor, w.policy, w.sampled_ids, w.uniforms, w.lam, w.k, 0, buf)
+        obrs.jp_obrs_rows(w.actor, w.policy, w.sampled_ids, w.uniforms, w.lam, w.k, args.flags & ~1, buf)
         b.record()
     torch.cuda.synchronize()
     row_ms = sorted(a.elapsed_time(b) for a, b in evs)
@@ -194,7 +197,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: T=%d, V=%d, bf16 logits, k=%d, lambda=%g, c1=c2=3"
                                % (w.name, T, V, w.k, w.lam),
-                   "logits_dtype": "bf16", "T": T, "V": V, "k": w.k, "lambda": w.lam,
+                   "logits_dtype": "bf16", "T": T, "V": V, "k": w.k, "lambda": w.lam, "flags": args.flags,
                    "kappa": st.kappa, "alpha_hat": st.alpha_hat},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

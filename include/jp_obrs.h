@@ -12,6 +12,7 @@
  *   alpha_hat  = accepted / proposed,  kappa = alpha_hat / mean_t Z_approx,t      Sec. 4.4.2
  *   w_t        = kappa Z_approx,t max(lambda, p(x_t)/q(x_t))          Alg. 1 step 3
  *   rho_t      = min(w_t, c1) min(p_ref(x_t)/p(x_t), c2)              Alg. 1 step 3
+ *   KL_t (optional) = sum_v p(v) (log p(v) - log q(v))                Sec. 4.2 (3), Eq. distill_loss
  *
  * Conventions
  *   - Every pointer argument is a DEVICE pointer unless it is a params / outputs struct
@@ -59,7 +60,8 @@ typedef enum jp_dtype { JP_F32 = 0, JP_BF16 = 1 } jp_dtype;
 enum {
     JP_FLAG_EXACT_Z = 1,        /* also compute Z over the whole vocabulary (second sweep)  */
     JP_FLAG_TOPK_LOGPROBS = 2,  /* also write log-probabilities of the two top-k lists      */
-    JP_FLAG_ALPHA_EXPECTED = 4  /* alpha_hat := mean_t a_t instead of accepted/proposed     */
+    JP_FLAG_ALPHA_EXPECTED = 4, /* alpha_hat := mean_t a_t instead of accepted/proposed     */
+    JP_FLAG_DISTILL_KL = 8      /* also compute the per-token distillation term KL(p || q)   */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */
@@ -87,6 +89,7 @@ typedef struct jp_obrs_stats {
     double mean_accept;         /* (1/B) sum_t a_t                                  */
     uint32_t error_flags;       /* JP_DATA_ERR_*                                    */
     uint32_t reserved;
+    double mean_distill_kl;     /* (1/B) sum_t KL(p_t || q_t), NaN without JP_FLAG_DISTILL_KL */
 } jp_obrs_stats;
 
 /* Output pointers (device memory, caller-owned).  NULL = not wanted. */
@@ -106,6 +109,9 @@ typedef struct jp_obrs_outputs {
     float *topk_actor_logq;     /* [T,k] log q of topk_actor,  with JP_FLAG_TOPK_LOGPROBS  */
     float *topk_policy_logp;    /* [T,k] log p of topk_policy, with JP_FLAG_TOPK_LOGPROBS  */
     jp_obrs_stats *stats;       /* one struct, written by the finalize stage               */
+    float *distill_kl;          /* [T]   KL(p_t || q_t) = sum_v p(v) (log p(v) - log q(v)), the
+                                         per-token on-policy distillation term of Sec. 4.2 (3),
+                                         Eq. distill_loss; with JP_FLAG_DISTILL_KL            */
 } jp_obrs_outputs;
 
 /* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */

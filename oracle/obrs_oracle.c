@@ -52,6 +52,8 @@ typedef struct {
     double kappa;               /* alpha_hat / mean_z_approx                    */
     double mean_z_exact;
     double mean_accept;         /* (1/B) sum_i a(x_i)                           */
+    double mean_kl_p_q;         /* (1/B) sum_i KL(p_i || q_i): the distillation loss value
+                                   of Sec. 4.2 (3), Eq. distill_loss                 */
 } jpo_batch_out;
 
 /* ---- exact widening of stored logits ---------------------------------- */
@@ -266,7 +268,7 @@ void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double l
                jpo_batch_out *b, double *w_out, double *rho_out)
 {
     memset(b, 0, sizeof *b);
-    double sz = 0.0, sze = 0.0, sa = 0.0;
+    double sz = 0.0, sze = 0.0, sa = 0.0, skl = 0.0;
     for (int64_t t = 0; t < T; ++t) {
         if (!rows[t].valid) continue;
         b->n_valid += 1;
@@ -274,12 +276,14 @@ void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double l
         sz += rows[t].z_approx;
         sze += rows[t].z_exact;
         sa += rows[t].accept;
+        skl += rows[t].kl_p_q;
     }
     double n = (double)b->n_valid;
     b->alpha_hat = (double)b->n_accept / n;
     b->mean_z_approx = sz / n;
     b->mean_z_exact = sze / n;
     b->mean_accept = sa / n;
+    b->mean_kl_p_q = skl / n;
     double alpha = use_expected_alpha ? b->mean_accept : b->alpha_hat;
     b->kappa = alpha / b->mean_z_approx;
 

@@ -37,7 +37,7 @@ class BatchOut(C.Structure):
         ("n_valid", C.c_int64), ("n_accept", C.c_int64),
         ("alpha_hat", C.c_double), ("mean_z_approx", C.c_double),
         ("kappa", C.c_double), ("mean_z_exact", C.c_double),
-        ("mean_accept", C.c_double),
+        ("mean_accept", C.c_double), ("mean_kl_p_q", C.c_double),
     ]
 
 

@@ -6,7 +6,7 @@
 
 namespace {
 
-constexpr uint32_t KNOWN_FLAGS = JP_FLAG_EXACT_Z | JP_FLAG_TOPK_LOGPROBS | JP_FLAG_ALPHA_EXPECTED;
+constexpr uint32_t KNOWN_FLAGS = JP_FLAG_EXACT_Z | JP_FLAG_TOPK_LOGPROBS | JP_FLAG_ALPHA_EXPECTED | JP_FLAG_DISTILL_KL;
 constexpr size_t ALIGN = 256;
 
 size_t round_up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
@@ -14,7 +14,7 @@ size_t round_up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
 // Scratch kept between the row stage and the batch stage (user buffers replace the float
 // arrays when the caller asked for those outputs).
 struct Workspace {
-    float *accept, *logq, *logp, *logratio, *zapprox, *zexact;
+    float *accept, *logq, *logp, *logratio, *zapprox, *zexact, *kl;
     double *lse_q, *lse_p;
     uint8_t *mask, *rowflag;
     jp_obrs_stats *stats;
@@ -34,6 +34,7 @@ Workspace carve(void *base, int64_t T)
     w.logratio = (float *)take(n * 4);
     w.zapprox = (float *)take(n * 4);
     w.zexact = (float *)take(n * 4);
+    w.kl = (float *)take(n * 4);
     w.lse_q = (double *)take(n * 8);
     w.lse_p = (double *)take(n * 8);
     w.mask = (uint8_t *)take(n);
@@ -89,6 +90,8 @@ jp_status rows_impl(const void *actor, const void *policy, int64_t T, int64_t V,
     a.logp = out->logp ? out->logp : w.logp;
     a.logratio = out->logratio ? out->logratio : w.logratio;
     a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+    a.distill = (prm->flags & JP_FLAG_DISTILL_KL) ? 1 : 0;
+    a.kl = out->distill_kl ? out->distill_kl : w.kl;
     a.lse_q = w.lse_q; a.lse_p = w.lse_p;
     a.mask = out->mask ? out->mask : w.mask;
     a.rowflag = w.rowflag;
@@ -132,6 +135,7 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
     f.logratio = out->logratio ? out->logratio : w.logratio;
     f.logp = out->logp ? out->logp : w.logp;
     f.ref_logprob = ref_logprob;
+    f.kl = (prm->flags & JP_FLAG_DISTILL_KL) ? (out->distill_kl ? out->distill_kl : w.kl) : nullptr;
     f.lambda = prm->lambda; f.c1 = prm->c1; f.c2 = prm->c2;
     f.alpha_expected = ((prm->flags & JP_FLAG_ALPHA_EXPECTED) || !have_uniforms) ? 1 : 0;
     f.stats = out->stats ? out->stats : w.stats;
@@ -215,6 +219,8 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
         a.logp = out->logp ? out->logp : w.logp;
         a.logratio = out->logratio ? out->logratio : w.logratio;
         a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+        a.distill = (prm->flags & JP_FLAG_DISTILL_KL) ? 1 : 0;
+        a.kl = out->distill_kl ? out->distill_kl : w.kl;
         a.lse_q = w.lse_q; a.lse_p = w.lse_p;
         a.mask = out->mask ? out->mask : w.mask;
         a.rowflag = w.rowflag;
@@ -298,6 +304,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 1; }
+int jp_obrs_abi_version(void) { return 2; }
 
 }  // extern "C"

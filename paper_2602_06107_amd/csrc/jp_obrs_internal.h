@@ -22,6 +22,8 @@ struct RowArgs {
     int k;
     // per-row results: never nullptr (user buffer or workspace)
     float *accept, *logq, *logp, *logratio, *zapprox;
+    float *kl;                        // KL(p || q) per token (distill != 0 only)
+    int distill;
     double *lse_q, *lse_p;
     uint8_t *mask, *rowflag;
     // optional user outputs
@@ -42,7 +44,8 @@ struct CarryHeader {
     double S[2];                      // sums of 2^(l log2e - M2)
     float x_logit[2];                 // logits of the sampled token, once its chunk has passed
     int have_x, pad;
-    unsigned char reserve[16];
+    double D;                         // sum of 2^(lp log2e - M2) (lp - lq), for the distillation term
+    unsigned char reserve[8];
 };
 static_assert(sizeof(CarryHeader) == 64, "carry header is 64 bytes");
 inline int carry_kc(int k) { return k <= 64 ? 64 : (k <= 128 ? 128 : 256); }
@@ -61,6 +64,7 @@ struct FinalizeArgs {
     int64_t T;
     const uint8_t *rowflag, *mask;
     const float *accept, *zapprox, *zexact, *logratio, *logp, *ref_logprob;
+    const float *kl;                  // nullptr unless the distillation term was requested
     float lambda, c1, c2;
     int alpha_expected;
     jp_obrs_stats *stats;

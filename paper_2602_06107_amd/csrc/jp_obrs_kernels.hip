@@ -255,6 +255,7 @@ template <class Key> struct Stream {
     float tauv;       // chunk maxima below this cannot enter the top-k
     Key tauk;         // exact form of the same bound (keys below it are not inserted)
     int cnt;          // descriptors currently buffered
+    float d;          // policy stream only: per-lane sum of 2^(lp*log2e - M2) * (lp - lq)
 };
 
 template <class KT, int C, int NS>
@@ -280,7 +281,9 @@ __device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typena
     if (__ballot(pass && cmax > st.mthr)) {
         float wm = uniform_f(wave_max(pass ? cmax : neg_inf()));
         float newM2 = wm * LOG2E_F;
-        st.s *= __builtin_amdgcn_exp2f(st.M2 - newM2);
+        const float rescale = __builtin_amdgcn_exp2f(st.M2 - newM2);
+        st.s *= rescale;
+        st.d *= rescale;
         st.M2 = newM2;
         st.mthr = wm + RESCALE_MARGIN2 / LOG2E_F;
     }
@@ -295,6 +298,26 @@ __device__ __forceinline__ double log2_of_sum(double S)
     const int e = __builtin_amdgcn_frexp_expf(f);            // f = m * 2^e, m in [0.5, 1)
     const float m2 = __builtin_amdgcn_frexp_mantf(f) * 2.0f;
     return (double)(e - 1) + (double)__builtin_amdgcn_logf(m2);
+}
+
+// Policy-row sum that also accumulates e_v (lp_v - lq_v), the numerator of the distillation
+// term KL(p || q) = sum_v p_v (lp_v - lq_v) - (LSE_p - LSE_q) (Sec. 4.2 (3), Eq. distill_loss).
+// lp_v = -inf gives e_v = 0; the difference is floored so that 0 * (-inf) cannot appear.
+template <int VEC>
+__device__ __forceinline__ float sum_exp2_kl(const float (&fp)[VEC], const float (&fq)[VEC], float M2, float &dacc)
+{
+    float a = 0.f, b = 0.f, da = 0.f, db = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; j += 2) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(fp[j], LOG2E_F, -M2));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(fp[j + 1], LOG2E_F, -M2));
+        a += e0;
+        b += e1;
+        da = __builtin_fmaf(e0, fmaxf(fp[j] - fq[j], -1.0e30f), da);
+        db = __builtin_fmaf(e1, fmaxf(fp[j + 1] - fq[j + 1], -1.0e30f), db);
+    }
+    dacc += da + db;
+    return a + b;
 }
 
 template <int VEC> __device__ __forceinline__ float max_of(const float (&f)[VEC])
@@ -342,7 +365,7 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // the running row state (exponent reference and sum of both rows, sampled-token logits, the two
 // top-k lists so far with both logits of every entry) is read from / written to a per-row record,
 // and only the launch of the last chunk runs the union / normaliser / acceptance step.
-template <class ET, class KT, int KC, bool CARRY>
+template <class ET, class KT, int KC, bool CARRY, bool DISTILL>
 __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
@@ -389,6 +412,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
             A.zapprox[t] = fill; A.lse_q[t] = fill; A.lse_p[t] = fill;
             if (A.mask) A.mask[t] = 0;
             if (A.usize) A.usize[t] = 0;
+            if (DISTILL) A.kl[t] = fill;
         }
         for (int r = lane; r < k; r += WAVE) {
             if (A.topk_a) A.topk_a[t * k + r] = -1;
@@ -417,7 +441,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         // Resume the scan: the carried sums go to lane 0, and a full carried list bounds what can
         // still enter the top-k (its k-th value), exactly as if the sweep had never stopped.
         sq.M2 = hdr->M2[0]; sp.M2 = hdr->M2[1];
-        if (lane == 0) { sq.s = (float)hdr->S[0]; sp.s = (float)hdr->S[1]; }
+        if (lane == 0) { sq.s = (float)hdr->S[0]; sp.s = (float)hdr->S[1]; sp.d = (float)hdr->D; }
         if (sq.M2 != M2_UNSET) sq.mthr = (sq.M2 + RESCALE_MARGIN2) / LOG2E_F;
         if (sp.M2 != M2_UNSET) sp.mthr = (sp.M2 + RESCALE_MARGIN2) / LOG2E_F;
         nl_in[0] = hdr->nl[0]; nl_in[1] = hdr->nl[1];
@@ -445,7 +469,8 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
             offer_chunk<KT, C, NS>(sp, s_desc1, mp, c, pp, k);
         }
         sq.s += sum_exp2<VEC>(fq, sq.M2);
-        sp.s += sum_exp2<VEC>(fp, sp.M2);
+        if constexpr (DISTILL) sp.s += sum_exp2_kl<VEC>(fp, fq, sp.M2, sp.d);
+        else sp.s += sum_exp2<VEC>(fp, sp.M2);
     };
 
     // ---- streaming sweep: iterations in which every lane owns a full 16-byte chunk ----------
@@ -492,6 +517,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
 
     // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
     const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
+    const double Dp = DISTILL ? wave_sum((double)sp.d) : 0.0;
     const double lse_q = ((double)sq.M2 + log2_of_sum(Sq)) * LN2_D;
     const double lse_p = ((double)sp.M2 + log2_of_sum(Sp)) * LN2_D;
     const double ln_lambda = A.ln_lambda;
@@ -634,7 +660,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
     if (carry_out) {                      // hand the row state to the launch of the next chunk
         if (lane == 0) {
             hdr->M2[0] = sq.M2; hdr->M2[1] = sp.M2;
-            hdr->S[0] = Sq; hdr->S[1] = Sp;
+            hdr->S[0] = Sq; hdr->S[1] = Sp; hdr->D = Dp;
             hdr->nl[0] = nl[0]; hdr->nl[1] = nl[1];
             hdr->x_logit[0] = xq; hdr->x_logit[1] = xp;
             hdr->have_x = (have_x || x_here) ? 1 : 0;
@@ -715,6 +741,8 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         A.zapprox[t] = finite_row ? (float)z_approx : NaN;
         if (A.mask) A.mask[t] = (finite_row && A.uni && (double)A.uni[t] < acc) ? 1 : 0;
         if (A.usize) A.usize[t] = usize;
+        // KL(p || q) = sum_v p_v (lp_v - lq_v) - (LSE_p - LSE_q)
+        if (DISTILL) A.kl[t] = finite_row ? (float)(Dp / Sp - (lse_p - lse_q)) : NaN;
     }
 }
 
@@ -771,11 +799,11 @@ constexpr int FINALIZE_WAVES = FINALIZE_THREADS / WAVE;
 
 __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs A)
 {
-    __shared__ double sh_z[FINALIZE_WAVES], sh_a[FINALIZE_WAVES], sh_ze[FINALIZE_WAVES];
+    __shared__ double sh_z[FINALIZE_WAVES], sh_a[FINALIZE_WAVES], sh_ze[FINALIZE_WAVES], sh_kl[FINALIZE_WAVES];
     __shared__ long long sh_n[FINALIZE_WAVES], sh_acc[FINALIZE_WAVES];
     __shared__ unsigned sh_err[FINALIZE_WAVES];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
-    double z = 0.0, a = 0.0, ze = 0.0;
+    double z = 0.0, a = 0.0, ze = 0.0, kl = 0.0;
     long long n = 0, nacc = 0;
     unsigned err = 0;
     // Inputs of this thread's first token of the weight pass, fetched before the reduction so
@@ -790,7 +818,7 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
     constexpr int U = 8;
     for (int64_t base = tid; base < A.T; base += (int64_t)U * FINALIZE_THREADS) {
         uint8_t f[U], mk[U];
-        float zv[U], av[U], zev[U];
+        float zv[U], av[U], zev[U], klv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t t = base + (int64_t)u * FINALIZE_THREADS;
@@ -800,6 +828,7 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
             zv[u] = in ? A.zapprox[t] : 0.f;
             av[u] = in ? A.accept[t] : 0.f;
             zev[u] = (in && A.zexact) ? A.zexact[t] : 0.f;
+            klv[u] = (in && A.kl) ? A.kl[t] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -809,6 +838,7 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
                 z += (double)zv[u];
                 a += (double)av[u];
                 ze += (double)zev[u];
+                kl += (double)klv[u];
             } else if (f[u] == ROW_BAD_ID) {
                 err |= JP_DATA_ERR_ID_RANGE;
             } else if (f[u] == ROW_NONFINITE) {
@@ -816,15 +846,15 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
             }
         }
     }
-    z = wave_sum(z); a = wave_sum(a); ze = wave_sum(ze);
+    z = wave_sum(z); a = wave_sum(a); ze = wave_sum(ze); kl = wave_sum(kl);
     n = wave_sum_i((int)n); nacc = wave_sum_i((int)nacc);      // per-thread counts are < 2^21
     err = wave_or(err);
-    if (lane == 0) { sh_z[wv] = z; sh_a[wv] = a; sh_ze[wv] = ze; sh_n[wv] = n; sh_acc[wv] = nacc; sh_err[wv] = err; }
+    if (lane == 0) { sh_z[wv] = z; sh_a[wv] = a; sh_ze[wv] = ze; sh_kl[wv] = kl; sh_n[wv] = n; sh_acc[wv] = nacc; sh_err[wv] = err; }
     __syncthreads();
-    z = a = ze = 0.0; n = nacc = 0; err = 0;
+    z = a = ze = kl = 0.0; n = nacc = 0; err = 0;
 #pragma unroll
     for (int i = 0; i < FINALIZE_WAVES; ++i) {
-        z += sh_z[i]; a += sh_a[i]; ze += sh_ze[i]; n += sh_n[i]; nacc += sh_acc[i]; err |= sh_err[i];
+        z += sh_z[i]; a += sh_a[i]; ze += sh_ze[i]; kl += sh_kl[i]; n += sh_n[i]; nacc += sh_acc[i]; err |= sh_err[i];
     }
     const double nn = (double)n;
     const double mean_z = z / nn, mean_a = a / nn;
@@ -841,6 +871,7 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
         st.mean_accept = mean_a;
         st.error_flags = err | (n == 0 ? (unsigned)JP_DATA_ERR_EMPTY : 0u);
         st.reserved = 0;
+        st.mean_distill_kl = A.kl ? kl / nn : __longlong_as_double(0x7ff8000000000000LL);
         *A.stats = st;
     }
     if (!A.w && !A.rho) return;
@@ -878,9 +909,15 @@ template <class ET, class KT>
 static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false>), grid, block, 0, st, a);
-    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false>), grid, block, 0, st, a);
+    if (a.distill) {
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, true>), grid, block, 0, st, a);
+        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, true>), grid, block, 0, st, a);
+    } else {
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false>), grid, block, 0, st, a);
+        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false>), grid, block, 0, st, a);
+    }
     return hipGetLastError();
 }
 
@@ -888,9 +925,15 @@ hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
     const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true>), grid, block, 0, st, a);
-    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true>), grid, block, 0, st, a);
+    if (a.distill) {
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, true>), grid, block, 0, st, a);
+        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, true>), grid, block, 0, st, a);
+    } else {
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, false>), grid, block, 0, st, a);
+        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, false>), grid, block, 0, st, a);
+    }
     return hipGetLastError();
 }
 

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("JP_OBRS_LIB", os.path.join(_PKG, "libjp_obrs.so"))   
 
 JP_K_MAX = 256
 JP_F32, JP_BF16 = 0, 1
-JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED = 1, 2, 4
+JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED, JP_FLAG_DISTILL_KL = 1, 2, 4, 8
 JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
 (JP_OK, JP_ERR_NULL, JP_ERR_SHAPE, JP_ERR_PARAM, JP_ERR_ALIGN, JP_ERR_WORKSPACE,
  JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
@@ -36,12 +36,13 @@ class Params(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("n_valid", C.c_int64), ("n_accept", C.c_int64), ("alpha_hat", C.c_double),
                 ("mean_z_approx", C.c_double), ("kappa", C.c_double), ("mean_z_exact", C.c_double),
-                ("mean_accept", C.c_double), ("error_flags", C.c_uint32), ("reserved", C.c_uint32)]
+                ("mean_accept", C.c_double), ("error_flags", C.c_uint32), ("reserved", C.c_uint32),
+                ("mean_distill_kl", C.c_double)]
 
 
 _OUT_FIELDS = ("accept_prob", "mask", "logq", "logp", "logratio", "z_approx", "z_exact", "w_obrs",
                "rho", "union_size", "topk_actor", "topk_policy", "topk_actor_logq",
-               "topk_policy_logp", "stats")
+               "topk_policy_logp", "stats", "distill_kl")
 
 
 class Outputs(C.Structure):
@@ -149,6 +150,8 @@ def alloc_buffers(T: int, V: int, k: int, dt: int, flags: int, device, want=None
             t[n] = torch.empty(T, **f32)
     if "z_exact" in names and (flags & JP_FLAG_EXACT_Z):
         t["z_exact"] = torch.empty(T, **f32)
+    if "distill_kl" in names and (flags & JP_FLAG_DISTILL_KL):
+        t["distill_kl"] = torch.empty(T, **f32)
     if "mask" in names:
         t["mask"] = torch.empty(T, dtype=torch.uint8, device=device)
     if "union_size" in names:

@@ -66,6 +66,8 @@ def check_rows(buf, w, R, rows=None, flags=0, tol=None):
     _close(g["z_approx"][v], o["z_approx"][v], tol, "Z_approx")
     if flags & obrs.JP_FLAG_EXACT_Z:
         _close(g["z_exact"][v], o["z_exact"][v], tol, "Z_exact")
+    if flags & obrs.JP_FLAG_DISTILL_KL:
+        _close(g["distill_kl"][v], o["kl_p_q"][v], tol, "KL(p||q)", abs_tol=tol)
     if flags & obrs.JP_FLAG_TOPK_LOGPROBS:
         a64 = wl.logits_to_float64(w.actor[torch.as_tensor(idx, device=w.actor.device)])
         p64 = wl.logits_to_float64(w.policy[torch.as_tensor(idx, device=w.actor.device)])
@@ -101,6 +103,10 @@ def check_batch(buf, w, R, g, flags=0, tol=None):
     _close(st.mean_accept, b.mean_accept, tol, "mean a")
     if flags & obrs.JP_FLAG_EXACT_Z:
         _close(st.mean_z_exact, b.mean_z_exact, tol, "mean Z_exact")
+    if flags & obrs.JP_FLAG_DISTILL_KL:
+        _close(st.mean_distill_kl, b.mean_kl_p_q, tol, "mean KL(p||q)", abs_tol=tol)
+    else:
+        assert np.isnan(st.mean_distill_kl)
     _close(g["w_obrs"], w_want, tol, "w_OBRS")
     _close(g["rho"], rho_want, tol, "rho")
     return st, b

@@ -21,24 +21,25 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize", "jp_obrs_workspace_bytes",
+            "jp_obrs_forward_lmhead", "jp_obrs_lmhead_workspace_bytes",
             "jp_status_string", "jp_obrs_abi_version"} <= set(names)
     lib = obrs.raw()
     for n in names:
         assert hasattr(lib, n), n
     assert set(obrs.EXPORTS) == set(names)
-    assert obrs.jp_obrs_abi_version() == 1
+    assert obrs.jp_obrs_abi_version() == 2
 
 
 def test_struct_layouts_match_header():
     assert C.sizeof(obrs.Params) == 20
-    assert C.sizeof(obrs.Stats) == 64
-    assert C.sizeof(obrs.Outputs) == 15 * C.sizeof(C.c_void_p)
+    assert C.sizeof(obrs.Stats) == 72
+    assert C.sizeof(obrs.Outputs) == 16 * C.sizeof(C.c_void_p)
 
 
 def test_workspace_bytes():
     f = obrs.jp_obrs_workspace_bytes
     assert f(0, 1024, 4, obrs.JP_F32) > 0
-    assert f(8192, 151936, 64, obrs.JP_BF16) >= 8192 * (6 * 4 + 2 * 8 + 2)
+    assert f(8192, 151936, 64, obrs.JP_BF16) >= 8192 * (7 * 4 + 2 * 8 + 2)
     assert f(8192, 151936, 64, obrs.JP_BF16) < 8192 * 64
     assert f(-1, 10, 1, obrs.JP_F32) == 0 and f(4, 0, 1, obrs.JP_F32) == 0 and f(4, 10, 1, 7) == 0
 

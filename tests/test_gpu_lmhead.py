@@ -44,6 +44,8 @@ def _check(w, buf, rows, flags=0, batch=True):
     pu._close(g["logp"], o["logp_x"], 0.0, "log p(x)", abs_tol=TOL)
     pu._close(g["logratio"], o["logratio"], 0.0, "log ratio", abs_tol=TOL)
     pu._close(g["accept_prob"], o["accept"], TOL, "a(x)")
+    if flags & obrs.JP_FLAG_DISTILL_KL:
+        pu._close(g["distill_kl"], o["kl_p_q"], TOL, "KL(p||q)", abs_tol=TOL)
     n_swapped = 0
     for i in range(len(rows)):
         for got, want, l in ((g["topk_actor"][i], R.topk_q[i], lq[i]), (g["topk_policy"][i], R.topk_p[i], lp[i])):
@@ -89,8 +91,9 @@ def test_lmhead_small_shapes(T, V, da, dp, k, chunk):
     print(f"lm_head T={T} V={V} d=({da},{dp}) k={k} chunk={chunk}", flush=True)
     w = wl.lm_head(T, V, da, dp, DEV, seed=100 + T, k=k).with_params(lam=1.2)
     w.ref_logprob = -torch.rand(T, device=DEV)
-    buf = _run(w, obrs.JP_FLAG_TOPK_LOGPROBS, chunk)
-    _check(w, buf, np.arange(T), obrs.JP_FLAG_TOPK_LOGPROBS)
+    flags = obrs.JP_FLAG_TOPK_LOGPROBS | obrs.JP_FLAG_DISTILL_KL
+    buf = _run(w, flags, chunk)
+    _check(w, buf, np.arange(T), flags)
 
 
 def test_lmhead_matches_materialised_path():

@@ -13,7 +13,7 @@ if torch.cuda.is_available():
     import parity_util as pu
 
 DEV = "cuda"
-ALL_FLAGS = 1 | 2      # exact Z + top-k log-probs
+ALL_FLAGS = 1 | 2 | 8  # exact Z + top-k log-probs + distillation KL
 
 
 def _say(msg):

@@ -405,3 +405,28 @@ def test_rows_driver_matches_single_rows_and_widens_exactly():
             if x[t] >= 0:
                 np.testing.assert_array_equal(R.topk_q[t], kq)
                 np.testing.assert_array_equal(R.topk_p[t], kp)
+
+
+# ---- distillation term (Sec. 4.2 (3), Eq. distill_loss): KL(p || q) per token, batch mean ---------
+
+def test_distillation_kl_against_scipy_rel_entr_and_batch_mean():
+    rng = np.random.default_rng(111)
+    V = 300
+    outs, want = [], []
+    for sigma in (0.0, 0.3, 1.0, 2.5):
+        lq = _rand_logits(rng, V)
+        lp = lq + rng.normal(0, sigma, V) if sigma > 0 else lq.copy()
+        q, p = _softmax64(lq), _softmax64(lp)
+        out, _, _ = orc.row(lq, lp, 0, 0.5, 1.0, 4)
+        kl = float(scipy.special.rel_entr(p, q).sum())
+        assert out.kl_p_q == pytest.approx(kl, rel=1e-10, abs=1e-14)
+        assert out.kl_p_q >= -1e-15                      # Gibbs' inequality
+        outs.append(out)
+        want.append(kl)
+    assert outs[0].kl_p_q == pytest.approx(0.0, abs=1e-15)      # p == q
+    outs.append(orc.row(lq, lp, -1, 0.5, 1.0, 4)[0])             # padding row is not averaged
+    b, _, _ = orc.batch(_rows_from(outs), [1] * 5, 1.0, 3.0, 3.0)
+    assert b.mean_kl_p_q == pytest.approx(sum(want) / 4, rel=1e-12)
+    # KL is not symmetric: swapping the roles of the two rows changes the value
+    out_sw, _, _ = orc.row(lp, lq, 0, 0.5, 1.0, 4)
+    assert abs(out_sw.kl_p_q - outs[3].kl_p_q) > 1e-3
