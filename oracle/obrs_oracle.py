@@ -65,7 +65,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        l = C.CDLL(build())
+        # JPO_ORACLE_LIB: a test may point this wrapper at a deliberately broken build of the
+        # oracle to show that the pin tests catch the planted mistake.
+        l = C.CDLL(os.environ.get("JPO_ORACLE_LIB") or build())
         l.jpo_logsumexp.restype = C.c_double
         l.jpo_logsumexp.argtypes = [C.c_void_p, C.c_int64]
         l.jpo_topk.restype = None

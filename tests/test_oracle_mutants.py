@@ -1,0 +1,71 @@
+"""The pins must bite: each plausible slip, planted in a copy of the oracle source (never in the
+oracle itself, and only on the CPU), has to make the pin suite fail."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "obrs_oracle.c")
+
+MUTANTS = [
+    ("acceptance uses q/p instead of p/q",
+     "double r = exp(out->logratio) / lambda;", "double r = exp(-out->logratio) / lambda;"),
+    ("acceptance forgets lambda",
+     "double r = exp(out->logratio) / lambda;", "double r = exp(out->logratio);"),
+    ("mask uses <= instead of <",
+     "out->mask = (u < out->accept) ? 1 : 0;", "out->mask = (u <= out->accept) ? 1 : 0;"),
+    ("kept mass divides q by lambda instead of p",
+     "double qv = exp(logq_v);\n    double pv = exp(logp_v) / lambda;",
+     "double qv = exp(logq_v) / lambda;\n    double pv = exp(logp_v);"),
+    ("kept mass takes the max",
+     "return qv < pv ? qv : pv;", "return qv > pv ? qv : pv;"),
+    ("ties go to the highest id",
+     "return (ia > ib) - (ia < ib);", "return (ia < ib) - (ia > ib);"),
+    ("top-k sorts ascending",
+     "if (va > vb) return -1;\n    if (va < vb) return 1;", "if (va > vb) return 1;\n    if (va < vb) return -1;"),
+    ("union counts a shared token twice",
+     "if (in_union[v]) {\n            z_approx += t;", "if (in_union[v]) {\n            z_approx += t * (double)in_union[v];"),
+    ("union forgets the policy list",
+     "for (int32_t j = 0; j < k; ++j) in_union[kp[j]] = 1;", ""),
+    ("log-sum-exp drops the max shift",
+     "return m + log(s);", "return log(s);"),
+    ("log-ratio has the wrong sign",
+     "out->logratio = out->logp_x - out->logq_x;", "out->logratio = out->logq_x - out->logp_x;"),
+    ("alpha_hat divides by all rows, padding included",
+     "b->alpha_hat = (double)b->n_accept / n;", "b->alpha_hat = (double)b->n_accept / (double)T;"),
+    ("kappa is inverted",
+     "b->kappa = alpha / b->mean_z_approx;", "b->kappa = b->mean_z_approx / alpha;"),
+    ("weight uses min(lambda, ratio)",
+     "double w = z_t * (lambda > ratio ? lambda : ratio);", "double w = z_t * (lambda < ratio ? lambda : ratio);"),
+    ("rho clips the reference factor from below",
+     "rho *= rr < c2 ? rr : c2;", "rho *= rr > c2 ? rr : c2;"),
+    ("KL(p||q) weights by q",
+     "kl_pq += pv * (logp_v - logq_v);", "kl_pq += exp(logq_v) * (logp_v - logq_v);"),
+]
+
+
+def test_mutant_snippets_exist_in_the_oracle():
+    src = open(SRC).read()
+    for name, old, _ in MUTANTS:
+        assert src.count(old) == 1, name
+    # the in_union marks are 0/1, so the "counted twice" mutant needs them to accumulate
+    assert "in_union[kq[j]] = 1;" in src
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_catch_planted_mistake(tmp_path, name, old, new):
+    src = open(SRC).read()
+    if name == "union counts a shared token twice":
+        src = src.replace("in_union[kq[j]] = 1;", "in_union[kq[j]] += 1;").replace("in_union[kp[j]] = 1;", "in_union[kp[j]] += 1;")
+    src = src.replace(old, new)
+    c = tmp_path / "mutant.c"
+    so = tmp_path / "libmutant.so"
+    c.write_text(src)
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", str(c), "-o", str(so), "-lm"], check=True)
+    env = dict(os.environ, JPO_ORACLE_LIB=str(so))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                        "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"no pin caught: {name}"
+    assert "failed" in r.stdout, r.stdout[-500:]
