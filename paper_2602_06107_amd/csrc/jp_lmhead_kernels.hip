@@ -22,10 +22,18 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
 
+typedef const __attribute__((address_space(1))) void *gvoid_ptr;
+typedef __attribute__((address_space(3))) void *lvoid_ptr;
+
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 256;
 constexpr int TILE_BYTES = BM * BK * 2;            // 32 KB per operand tile
 constexpr int ROW_BYTES = BK * 2;                  // 128 B: eight 16-byte pieces per tile row
+constexpr int NU = 5;                              // LDS ring: five operand-tile slots, the whole 160 KB
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+constexpr int WAIT_VM0 = 0x0F70;                   // vmcnt(0)
+constexpr int WAIT_VM8_LGKM0 = 0x0078;             // vmcnt(8) lgkmcnt(0)
+constexpr int WAIT_VM24 = 0x4F78;                  // vmcnt(24)
 
 // Piece p (0..7) of tile row r is stored at piece p ^ ((r >> 1) & 7).  The LDS serves 256 bytes
 // (64 banks) per cycle, i.e. 16 lanes of a 16-byte access: consecutive rows alternate between the
@@ -64,10 +72,17 @@ __global__ __launch_bounds__(256) void transpose_chunk_kernel(const uint16_t *__
 // C[m, n] = sum_k A[m, k] * Bt[n, k]; A: [M, K] bf16, Bt: [N, K] bf16, C: [M, ldc] fp32.
 // K is a multiple of 64 and N a multiple of 256 (the caller pads Bt with zero rows); M is free.
 // blockIdx.z selects one of two independent problems (policy / actor head) sharing M, N, ldc.
+//
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging
+// registers, no ds_write).  A wave instruction of that kind writes 64 x 16 bytes to consecutive
+// LDS addresses, which is 8 tile rows of 128 bytes (whole cache lines on the global side); the
+// swizzle is applied on the global side (which 16-byte piece of its row a lane fetches), so the
+// LDS image is the same as if it had been written piece by piece.  The operand tiles of
+// successive k-tiles, A(0) B(0) A(1) B(1) ..., go round a ring of five 32 KB slots.
 // -------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // 2 stages x (A tile, B tile)
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // NS stages x (A tile, B tile)
     const int z = blockIdx.z;
     const unsigned char *A = (const unsigned char *)G.A[z];
     const unsigned char *B = (const unsigned char *)G.Bt[z];
@@ -94,24 +109,44 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
     const int tile_m = group * GM + in_group % gm;
     const int tile_n = in_group / gm;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;                 // 2 x 2 waves, 128 x 128 each
     const int li = lane & 31, lg = lane >> 5;                // MFMA row/col index, k-group
 
-    // staging: thread owns piece (tid & 7) of rows (tid >> 3) + 32 i, i < 8, of both tiles
-    const int sp = tid & 7, sr = tid >> 3;
+    // Loads: per operand tile a wave fetches tile rows [64 wave + 8 i, +8), i < 8.  Lane l lands at
+    // LDS piece (l & 7) of row (l >> 3) of that group, so it fetches logical piece
+    // (l & 7) ^ swizzle(row), and swizzle(row) = (row >> 1) & 7 = 4 (i & 1) + ((l >> 4) & 3).
     const int64_t ldk = (int64_t)K * 2;                      // bytes per row of A / Bt
     const unsigned char *abase = A + (int64_t)tile_m * BM * ldk;     // wave-uniform tile origins
     const unsigned char *bbase = B + (int64_t)tile_n * BN * ldk;
-    uint32_t oa[8], ob[8];                                   // byte offsets inside the tile's rows
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int ra = sr + 32 * i;
+    uint32_t oa[8], ob[8];                                   // byte offsets of this lane's pieces
+    {
         const int last = M - 1 - tile_m * BM;                // rows past M repeat the last row (never stored)
-        ra = ra < last ? ra : last;
-        oa[i] = (uint32_t)ra * (uint32_t)ldk + sp * 16;
-        ob[i] = (uint32_t)(sr + 32 * i) * (uint32_t)ldk + sp * 16;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int piece = (lane & 7) ^ (4 * (i & 1) + ((lane >> 4) & 3));
+            const int r = wave * 64 + i * 8 + (lane >> 3);
+            const int ra = r < last ? r : last;
+            oa[i] = (uint32_t)ra * (uint32_t)ldk + piece * 16;
+            ob[i] = (uint32_t)r * (uint32_t)ldk + piece * 16;
+        }
     }
+    const int nk = K / BK;
+    // quarter q (0..3) of the loads of operand tile `which` (0 = A, 1 = B) of k-tile kt into ring slot `slot`
+    auto issue_quarter = [&](int which, int kt, int slot, int q) __attribute__((always_inline)) {
+        const int kc = kt < nk ? kt : nk - 1;                // past the end: a harmless repeat into a free slot
+        unsigned char *dst = lds + slot * TILE_BYTES + wave * 8192;
+#pragma unroll
+        for (int i = 2 * q; i < 2 * q + 2; ++i) {
+            const unsigned char *src = which ? bbase + ob[i] : abase + oa[i];
+            __builtin_amdgcn_global_load_lds((gvoid_ptr)(uintptr_t)(src + kc * ROW_BYTES), (lvoid_ptr)(dst + i * 1024), 16, 0, 0);
+        }
+    };
+    auto issue_tile = [&](int which, int kt, int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) issue_quarter(which, kt, slot, q);
+    };
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -121,72 +156,87 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // Global -> register -> LDS staging with the memory instructions spread between the MFMAs:
-    // during k-tile kt the 16 ds_writes that put tile kt+1 (already in registers) into the other
-    // LDS stage ride behind the first 32 MFMAs, and the 16 global loads of tile kt+2 ride behind
-    // the last 32, so neither the vector-memory nor the LDS queue ever stalls the matrix pipe and
-    // every load has about one and a half k-tiles (~1.3 us) to arrive.
-    u32x4 stg[16];                                           // pieces 0-7: A rows, 8-15: Bt rows
-    const int nk = K / BK;
-    const uint32_t st_off = (uint32_t)tile_offset(sr, sp);   // rows 32 apart share their swizzle
-    auto gload_piece = [&](int kt, int p) __attribute__((always_inline)) {
-        const int kc = kt < nk ? kt : nk - 1;                // past the end: a harmless repeat
-        stg[p] = p < 8 ? *(gvec_ptr)(uintptr_t)(abase + oa[p] + kc * ROW_BYTES)
-                       : *(gvec_ptr)(uintptr_t)(bbase + ob[p - 8] + kc * ROW_BYTES);
-    };
-    auto lstore_piece = [&](int stage, int p) __attribute__((always_inline)) {
-        unsigned char *t = lds + stage * 2 * TILE_BYTES + st_off + (p < 8 ? 0 : TILE_BYTES) + (p & 7) * 32 * ROW_BYTES;
-        *(u32x4 *)t = stg[p];
-    };
-    uint32_t fa_off[BK / 16], fb_off[BK / 16];               // fragment addresses of the 4 k-steps
+    uint32_t fa_off[4], fb_off[4];                           // fragment addresses of the four k-steps
 #pragma unroll
-    for (int s2 = 0; s2 < BK / 16; ++s2) {
+    for (int s2 = 0; s2 < 4; ++s2) {
         fa_off[s2] = (uint32_t)tile_offset(wm * 128 + li, 2 * s2 + lg);
-        fb_off[s2] = (uint32_t)(TILE_BYTES + tile_offset(wn * 128 + li, 2 * s2 + lg));
+        fb_off[s2] = (uint32_t)tile_offset(wn * 128 + li, 2 * s2 + lg);
     }
-
+    bf16x8 fa[2][4], fb[2][4];
+    auto lfrag = [&](int slot_a, int slot_b, int s2) __attribute__((always_inline)) {
+        const unsigned char *ta = lds + slot_a * TILE_BYTES, *tb = lds + slot_b * TILE_BYTES;
 #pragma unroll
-    for (int p = 0; p < 16; ++p) gload_piece(0, p);
-#pragma unroll
-    for (int p = 0; p < 16; ++p) lstore_piece(0, p);
-#pragma unroll
-    for (int p = 0; p < 16; ++p) gload_piece(1, p);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt & 1;
-        const unsigned char *ts = lds + stage * 2 * TILE_BYTES;
-        bf16x8 fa[2][4], fb[2][4];
-        auto lfrag = [&](int s2, int b2) __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                fa[b2][i] = *(const bf16x8 *)(ts + fa_off[s2] + i * 32 * ROW_BYTES);
-                fb[b2][i] = *(const bf16x8 *)(ts + fb_off[s2] + i * 32 * ROW_BYTES);
-            }
-        };
-        lfrag(0, 0);
-#pragma unroll
-        for (int s2 = 0; s2 < BK / 16; ++s2) {
-            if (s2 + 1 < BK / 16) lfrag(s2 + 1, (s2 + 1) & 1);   // fragments one k-step ahead
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s2 & 1][i], fb[s2 & 1][j], acc[i][j], 0, 0, 0);
-                const int r = s2 * 4 + i;                    // 16 MFMA rows per k-tile
-                if (r < 8) {
-                    lstore_piece(stage ^ 1, 2 * r);
-                    lstore_piece(stage ^ 1, 2 * r + 1);
-                } else {
-                    gload_piece(kt + 2, 2 * (r - 8));
-                    gload_piece(kt + 2, 2 * (r - 8) + 1);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int i = 0; i < 4; ++i) {
+            fa[s2 & 1][i] = *(const bf16x8 *)(ta + fa_off[s2] + i * 32 * ROW_BYTES);
+            fb[s2 & 1][i] = *(const bf16x8 *)(tb + fb_off[s2] + i * 32 * ROW_BYTES);
         }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mfma_row = [&](int s2, int i) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s2 & 1][i], fb[s2 & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto ring_next = [](int slot, int by) { slot += by; return slot >= NU ? slot - NU : slot; };
+
+    // Ring schedule.  While k-tile kt is multiplied out of slots sa (A) and sb (B), the slots
+    // after them hold A(kt+1), B(kt+1) and A(kt+2), landed or in flight.  Late in tile kt, once
+    // its last fragments are in registers, every wave waits for its own share of tile kt+1 (all
+    // but the newest 8 loads, which are A(kt+2)); the barrier makes every wave's share visible
+    // and proves that nobody reads the slots of tile kt any more, which then take B(kt+2) and
+    // A(kt+3).  Fragment reads are issued a whole k-step before they are used, and the loads are
+    // dealt out four at a time between MFMA rows.
+    int sa = 0, sb = 1;
+    issue_tile(0, 0, 0);
+    issue_tile(1, 0, 1);
+    issue_tile(0, 1, 2);
+    issue_tile(1, 1, 3);
+    issue_tile(0, 2, 4);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM24);
+    __syncthreads();
+    lfrag(sa, sb, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int sa1 = ring_next(sa, 2), sb1 = ring_next(sb, 2);
+        mfma_row(0, 0);
+        lfrag(sa, sb, 1);
+        mfma_row(0, 1);
+        mfma_row(0, 2);
+        mfma_row(0, 3);
+        mfma_row(1, 0);
+        lfrag(sa, sb, 2);
+        mfma_row(1, 1);
+        mfma_row(1, 2);
+        mfma_row(1, 3);
+        mfma_row(2, 0);
+        lfrag(sa, sb, 3);
+        mfma_row(2, 1);
+        mfma_row(2, 2);
+        __builtin_amdgcn_s_waitcnt(WAIT_VM8_LGKM0);
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_row(2, 3);
+        lfrag(sa1, sb1, 0);                                  // past the end: reads a stale slot, unused
+        mfma_row(3, 0);
+        issue_quarter(1, kt + 2, sa, 0);                     // B(kt+2) takes A(kt)'s slot,
+        issue_quarter(1, kt + 2, sa, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_row(3, 1);
+        issue_quarter(1, kt + 2, sa, 2);
+        issue_quarter(1, kt + 2, sa, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_row(3, 2);
+        issue_quarter(0, kt + 3, sb, 0);                     // A(kt+3) takes B(kt)'s slot
+        issue_quarter(0, kt + 3, sb, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_row(3, 3);
+        issue_quarter(0, kt + 3, sb, 2);
+        issue_quarter(0, kt + 3, sb, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        sa = sa1;
+        sb = sb1;
     }
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0);                    // no load may still be writing LDS at exit
 
     // D layout of the 32x32 MFMA: lane holds column (lane & 31); register r is row
     // 8 (r / 4) + 4 (lane >> 5) + (r & 3).
@@ -215,7 +265,7 @@ hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0,
 
 hipError_t launch_gemm_pair(const GemmArgs &g, hipStream_t st)
 {
-    const int lds_bytes = 4 * TILE_BYTES;      // 128 KB: two stages of an A tile and a B tile
+    const int lds_bytes = NU * TILE_BYTES;      // 160 KB ring
     hipError_t e = hipFuncSetAttribute((const void *)gemm_tn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     const int tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
