@@ -131,6 +131,62 @@ __device__ __forceinline__ unsigned wave_or(unsigned v)
 // moving LDS accesses across it).
 __device__ __forceinline__ void lds_sync() { __syncthreads(); }
 
+// Value of lane (lane ^ L): data-parallel primitives inside a row of 16 lanes where one exists,
+// the LDS crossbar (no memory access) otherwise.
+template <int L> __device__ __forceinline__ uint32_t xor_lane(uint32_t v)
+{
+    static_assert(L == 1 || L == 2 || L == 4 || L == 8 || L == 16 || L == 32, "lane distance");
+    if constexpr (L == 1) return (uint32_t)dpp_mov<DPP_QUAD_XOR1>((int)v);
+    else if constexpr (L == 2) return (uint32_t)dpp_mov<DPP_QUAD_XOR2>((int)v);
+    else if constexpr (L == 8) return (uint32_t)dpp_mov<DPP_ROW_ROR8>((int)v);
+    else if constexpr (L == 32) return (uint32_t)__builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 32u) << 2), (int)v);
+    else return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (L << 10));   // bit mode: and 0x1f, or 0, xor L
+}
+template <int L> __device__ __forceinline__ uint64_t xor_lane(uint64_t v)
+{
+    return ((uint64_t)xor_lane<L>((uint32_t)(v >> 32)) << 32) | xor_lane<L>((uint32_t)v);
+}
+
+// Bitonic sorting network over the 64 * R keys of a wave, descending; key e of the sequence is
+// register (e % R) of lane (e / R), so the exchanges at distance < R stay inside a lane.
+template <class SK, int R, int K2, int J> __device__ __forceinline__ void bitonic_layer(SK (&v)[R], int lane)
+{
+    if constexpr (J < R) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if ((r & J) == 0) {
+                const bool desc = (K2 < R) ? ((r & K2) == 0) : ((lane & (K2 / R)) == 0 || K2 == WAVE * R);
+                const SK a = v[r], b = v[r | J];
+                const bool g = a > b;
+                const SK hi = g ? a : b, lo = g ? b : a;
+                v[r] = desc ? hi : lo;
+                v[r | J] = desc ? lo : hi;
+            }
+        }
+    } else {
+        constexpr int L = J / R;
+        const bool lower = (lane & L) == 0;
+        const bool desc = (lane & (K2 / R)) == 0 || K2 == WAVE * R;
+        const bool keep_max = lower == desc;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const SK p = xor_lane<L>(v[r]);
+            const bool g = v[r] > p;
+            v[r] = (g == keep_max) ? v[r] : p;
+        }
+    }
+    if constexpr (J > 1) bitonic_layer<SK, R, K2, J / 2>(v, lane);
+}
+template <class SK, int R, int K2> __device__ __forceinline__ void bitonic_merge_from(SK (&v)[R], int lane)
+{
+    bitonic_layer<SK, R, K2, K2 / 2>(v, lane);
+    if constexpr (K2 < WAVE * R) bitonic_merge_from<SK, R, K2 * 2>(v, lane);
+}
+template <class SK, int R> __device__ __forceinline__ void bitonic_sort_desc(SK (&v)[R], int lane)
+{
+    bitonic_merge_from<SK, R, 2>(v, lane);
+}
+
 // ---- element types ------------------------------------------------------------------------
 
 struct Bf16Elem {
@@ -147,6 +203,18 @@ struct Bf16Elem {
     {
         return __uint_as_float((uint32_t)((const uint16_t *)row)[i] << 16);
     }
+    // Candidate key for the final ranking: 16 value bits, then the complement of the candidate's
+    // position in the buffer.  Candidates are buffered in ascending id order, so an unsigned
+    // compare orders the keys by (value desc, id asc).
+    using SortKey = uint32_t;
+    static __device__ __forceinline__ SortKey make_sort(uint32_t ord, uint32_t pos) { return (ord & 0xffff0000u) | (0xffffu - pos); }
+    static __device__ __forceinline__ uint32_t sort_ord(SortKey k) { return k & 0xffff0000u; }
+    static __device__ __forceinline__ uint32_t sort_pos(SortKey k) { return 0xffffu - (k & 0xffffu); }
+    static __device__ __forceinline__ float sort_value(SortKey k)
+    {
+        const uint32_t o = k & 0xffff0000u;
+        return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : (~o & 0xffff0000u));
+    }
 };
 
 struct F32Elem {
@@ -158,6 +226,11 @@ struct F32Elem {
         f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
     }
     static __device__ __forceinline__ float load1(const char *row, int64_t i) { return ((const float *)row)[i]; }
+    using SortKey = uint64_t;               // 32 value bits, then the complement of the position
+    static __device__ __forceinline__ SortKey make_sort(uint32_t ord, uint32_t pos) { return ((uint64_t)ord << 32) | (uint64_t)(0xffffffffu - pos); }
+    static __device__ __forceinline__ uint32_t sort_ord(SortKey k) { return (uint32_t)(k >> 32); }
+    static __device__ __forceinline__ uint32_t sort_pos(SortKey k) { return 0xffffffffu - (uint32_t)k; }
+    static __device__ __forceinline__ float sort_value(SortKey k) { return unord32((uint32_t)(k >> 32)); }
 };
 
 // ---- chunk descriptors: (chunk maximum, chunk index) packed so that an unsigned compare orders
@@ -366,28 +439,35 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // top-k lists so far with both logits of every entry) is read from / written to a per-row record,
 // and only the launch of the last chunk runs the union / normaliser / acceptance step.
 template <class ET, class KT, int KC, bool CARRY, bool DISTILL>
-__global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
+__global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
-    constexpr int C = 4 * KC;             // descriptor buffer capacity per tensor
+    constexpr int C = (KC >= 256 ? 3 : 4) * KC;   // descriptor buffer capacity per tensor
     constexpr int NS = C / WAVE;
-    constexpr int E = 2 * KC + WAVE;      // element candidate capacity
-    constexpr int ES = E / WAVE;
+    constexpr int E = 2 * KC;             // element candidate capacity = keys of the sorting network
+    constexpr int R = E / WAVE;
+    using SK = typename ET::SortKey;
 
     // One LDS pool, used twice: during the sweep it holds the two descriptor buffers; once the
     // surviving descriptors sit in registers it holds the element candidates of the expansion.
     constexpr int DS = 2 * KC / WAVE;                               // descriptor registers per lane
     constexpr int DESC_BYTES = 2 * C * (int)sizeof(Key);
-    constexpr int CAND_BYTES = (E + 2) * 8 + E * 4;
+    constexpr int CAND_BYTES = E * ((int)sizeof(SK) + 8);
     constexpr int POOL_BYTES = ((DESC_BYTES > CAND_BYTES ? DESC_BYTES : CAND_BYTES) + 15) / 16 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char pool[POOL_BYTES];
     Key *const s_desc0 = (Key *)pool;
     Key *const s_desc1 = s_desc0 + C;
-    uint64_t *const s_key = (uint64_t *)pool;                       // (ord32(value) << 32) | ~id
-    uint32_t *const s_oth = (uint32_t *)(pool + (E + 2) * 8);       // the other tensor's logit
-    __shared__ uint32_t l_id[2][KC];
-    __shared__ float l_a[2][KC], l_b[2][KC];
+    SK *const s_key = (SK *)pool;                                   // candidate sort keys
+    uint32_t *const s_cid = (uint32_t *)(pool + E * sizeof(SK));    // candidate token ids
+    uint32_t *const s_oth = s_cid + E;                              // the other tensor's logit
+    // The two ranked lists (ids, own logits, the other tensor's logits).  List 1 is only written
+    // when the candidates of tensor 1 are no longer needed and takes their place in the pool.
+    __shared__ uint32_t list0[3 * KC];
+    static_assert(POOL_BYTES >= (3 * KC + 2 * KC) * 4, "list 1 and the union hash table share the pool");
+    uint32_t *const l_id[2] = {list0, (uint32_t *)pool};
+    float *const l_a[2] = {(float *)(list0 + KC), (float *)pool + KC};
+    float *const l_b[2] = {(float *)(list0 + 2 * KC), (float *)pool + 2 * KC};
 
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
@@ -554,16 +634,21 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
     int nl[2];
     auto expand = [&](auto tensor_c) {
         constexpr int i = decltype(tensor_c)::value;
-        const char *rowA = i == 0 ? rowq : rowp;
-        const char *rowB = i == 0 ? rowp : rowq;
+        const char *rowA = i == 0 ? rowq : rowp;     // the tensor ranked here
+        const char *rowB = i == 0 ? rowp : rowq;     // the other one
+        // A candidate needs ord >= thr_ord (the k-th largest chunk maximum) and, once k candidates
+        // have been ranked, ord > above_ord (their k-th value: all of them have smaller ids).
         uint32_t thr_ord = (nc[i] >= k) ? KT::ord(uniform_key<Key>(kth[i])) : 0u;
+        uint32_t above_ord = 0u;
+        bool have_above = false;
         int nS = 0;
         if (CARRY && nl_in[i] > 0) {
-            // The carried list seeds the candidates; when it is full its k-th value is a second
-            // lower bound of the final k-th value.
+            // The carried list seeds the candidates (all its ids are below this chunk's); when it
+            // is full its k-th value is a second lower bound of the final k-th value.
             const uint32_t *cid = st_id0 + (i * 3 + 0) * KC, *ca = cid + KC, *cb = ca + KC;
             for (int r = lane; r < nl_in[i]; r += WAVE) {
-                s_key[r] = ((uint64_t)ord32(__uint_as_float(ca[r])) << 32) | (uint64_t)(0xffffffffu - cid[r]);
+                s_key[r] = ET::make_sort(ord32(__uint_as_float(ca[r])), (uint32_t)r);
+                s_cid[r] = cid[r];
                 s_oth[r] = cb[r];
             }
             nS = nl_in[i];
@@ -573,86 +658,146 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
             }
         }
 
-        // Rank the nS buffered candidates; the best min(nS, k) go to list i in rank order.
-        auto rank_slots = [&](auto nslots_c) {
-            constexpr int N = decltype(nslots_c)::value;
-            uint64_t mykey[N];
-            int rank[N];
+        // The other tensor's logit of a candidate is fetched once the candidate set is known
+        // (entries [filled, nS) still lack it); the loads of one pass are independent.
+        int filled = nS;
+        auto fill_other = [&]() {
+            lds_sync();
+            for (int e = filled + lane; e < nS; e += WAVE)
+                s_oth[e] = __float_as_uint(ET::load1(rowB, (int64_t)s_cid[e] - id_base));
+            filled = nS;
+        };
+        // Sort the nS buffered candidates.  Candidates are buffered in ascending id order among
+        // equal values, and the key carries the buffer position, so the descending sort is the
+        // (value desc, id asc) order.  Lane l ends up with ranks l R .. l R + R - 1 and the id and
+        // other-tensor logit that go with them.
+        SK v[R];
+        uint32_t gid[R], goth[R];
+        auto sort_candidates = [&]() {
+            lds_sync();
 #pragma unroll
-            for (int s = 0; s < N; ++s) {
-                const int e = s * WAVE + lane;
-                mykey[s] = (e < nS) ? s_key[e] : ~(uint64_t)0;
-                rank[s] = 0;
+            for (int r = 0; r < R; ++r) {
+                const int e = lane * R + r;
+                v[r] = e < nS ? s_key[e] : (SK)0;
             }
-            for (int j = 0; j < nS; j += 2) {          // s_key[nS] is a zero pad
-                const u64x2 kj = *(const u64x2 *)&s_key[j];
+            bitonic_sort_desc<SK, R>(v, lane);
+            const int keep = nS < k ? nS : k;
 #pragma unroll
-                for (int s = 0; s < N; ++s) rank[s] += (kj.x > mykey[s] ? 1 : 0) + (kj.y > mykey[s] ? 1 : 0);
+            for (int r = 0; r < R; ++r) {
+                uint32_t pos = ET::sort_pos(v[r]);
+                pos = pos < (uint32_t)(E - 1) ? pos : (uint32_t)(E - 1);
+                const bool live = lane * R + r < keep;
+                gid[r] = live ? s_cid[pos] : 0u;
+                goth[r] = live ? s_oth[pos] : 0u;
             }
+            lds_sync();                                   // everything needed from the buffer is in registers
+            return keep;
+        };
+        // Make room: keep only the k best so far, in rank order (which keeps equal values in id order).
+        auto compact = [&]() {
+            fill_other();
+            const int keep = sort_candidates();
 #pragma unroll
-            for (int s = 0; s < N; ++s) {
-                const int e = s * WAVE + lane;
-                if (e < nS && rank[s] < k) {
-                    l_id[i][rank[s]] = 0xffffffffu - (uint32_t)mykey[s];
-                    l_a[i][rank[s]] = unord32((uint32_t)(mykey[s] >> 32));
-                    l_b[i][rank[s]] = __uint_as_float(s_oth[e]);
+            for (int r = 0; r < R; ++r) {
+                const int q = lane * R + r;
+                if (q < keep) {
+                    s_key[q] = ET::make_sort(ord32(ET::sort_value(v[r])), (uint32_t)q);
+                    s_cid[q] = gid[r];
+                    s_oth[q] = goth[r];
                 }
             }
-        };
-        auto rank_to_list = [&]() {
-            if (lane == 0) s_key[nS] = 0;
+            nS = keep;
+            filled = keep;
             lds_sync();
-            // one instantiation per number of 64-entry slots actually in use
-            auto pick = [&](auto self, auto n_c) -> void {
-                constexpr int N = decltype(n_c)::value;
-                if constexpr (N >= ES) rank_slots(std::integral_constant<int, ES>{});
-                else if (nS <= N * WAVE) rank_slots(n_c);
-                else self(self, std::integral_constant<int, N + 1>{});
-            };
-            pick(pick, std::integral_constant<int, 1>{});
-            lds_sync();
+            if (keep >= k) {
+                const SK kk = s_key[k - 1];
+                above_ord = uniform_u(ord32(ET::sort_value(kk)));
+                have_above = true;
+            }
         };
 
+        // The surviving chunks of this tensor are requested up to four per lane at a time, before
+        // the first of them is looked at.
+        constexpr int PF = DS > 4 ? 4 : DS;
+        u32x4 raw[PF];
 #pragma unroll
         for (int sl = 0; sl < DS; ++sl) {
             if (sl * WAVE >= nc[i]) break;
+            if (sl % PF == 0) {
+#pragma unroll
+                for (int u = 0; u < PF; ++u) {
+                    const bool full = (sl + u) * WAVE + lane < nc[i] && KT::chunk(dk[i][sl + u]) < nfull;
+                    raw[u] = full ? as_global_vec(rowA)[KT::chunk(dk[i][sl + u])] : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
             const bool has = sl * WAVE + lane < nc[i];
             const uint32_t c = has ? KT::chunk(dk[i][sl]) : 0u;
-            float fa[VEC], fb[VEC];
-            if (has) {
-                load_chunk<ET>(rowA, c, nfull, tail, fa);
-                load_chunk<ET>(rowB, c, nfull, tail, fb);
+            float fa[VEC];
+            if (has && c < nfull) {
+                ET::unpack(raw[sl % PF], fa);
+            } else if (has) {
+                load_chunk<ET>(rowA, c, nfull, tail, fa);            // the ragged last chunk
             } else {
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) { fa[j] = neg_inf(); fb[j] = neg_inf(); }
+                for (int j = 0; j < VEC; ++j) fa[j] = neg_inf();
             }
+            // bit j: element j of this lane's chunk is a candidate
+            auto candidates = [&](bool mine) {
+                uint32_t m = 0;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                if (nS + WAVE > E) {          // make room: keep only the k best so far
-                    rank_to_list();
-                    const int keep = nS < k ? nS : k;
-                    for (int r = lane; r < keep; r += WAVE) {
-                        s_key[r] = ((uint64_t)ord32(l_a[i][r]) << 32) | (uint64_t)(0xffffffffu - l_id[i][r]);
-                        s_oth[r] = __float_as_uint(l_b[i][r]);
+                for (int j = 0; j < VEC; ++j) {
+                    const uint32_t o = ord32(fa[j]);
+                    const bool ok = mine && (int64_t)c * VEC + j < V && o >= thr_ord && (!have_above || o > above_ord);
+                    m |= ok ? (1u << j) : 0u;
+                }
+                return m;
+            };
+            // Descriptors are in ascending chunk order, so appending lane by lane, element by
+            // element keeps the buffer in ascending id order.
+            auto append = [&](uint32_t m) {
+                const int cnt = __popc(m);
+                int pre = 0, tot = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint64_t bm = __ballot((cnt >> b) & 1);
+                    pre += lane_prefix(bm) << b;
+                    tot += __popcll(bm) << b;
+                }
+                uint32_t pos = (uint32_t)(nS + pre);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    if ((m >> j) & 1u) {
+                        s_key[pos] = ET::make_sort(ord32(fa[j]), pos);
+                        s_cid[pos] = (uint32_t)(id_base + (int64_t)c * VEC + j);
+                        ++pos;
                     }
-                    nS = keep;
-                    lds_sync();
                 }
-                const int64_t lid = (int64_t)c * VEC + j;
-                const int64_t id = id_base + lid;
-                const uint32_t o = ord32(fa[j]);
-                const bool ok = has && lid < V && o >= thr_ord;
-                const uint64_t m = __ballot(ok);
-                if (ok) {
-                    const int pos = nS + lane_prefix(m);
-                    s_key[pos] = ((uint64_t)o << 32) | (uint64_t)(0xffffffffu - (uint32_t)id);
-                    s_oth[pos] = __float_as_uint(fb[j]);
+                nS += tot;
+            };
+            const uint32_t m_all = candidates(has);
+            if (nS + wave_sum_i(__popc(m_all)) <= E) {
+                append(m_all);
+            } else {
+                // Too many for the buffer at once: eight lanes (at most 64 candidates) at a time,
+                // ranking and keeping the k best whenever the next group might not fit.
+                for (int g = 0; g < WAVE / 8; ++g) {
+                    if (nS + WAVE > E) compact();
+                    append(candidates(has && (lane >> 3) == g));
                 }
-                nS += __popcll(m);
             }
         }
-        rank_to_list();
-        nl[i] = nS < k ? nS : k;
+        fill_other();
+        nl[i] = sort_candidates();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int q = lane * R + r;
+            if (q < nl[i]) {
+                l_id[i][q] = gid[r];
+                l_a[i][q] = ET::sort_value(v[r]);
+                l_b[i][q] = __uint_as_float(goth[r]);
+            }
+        }
+        lds_sync();
     };
     expand(std::integral_constant<int, 0>{});
     expand(std::integral_constant<int, 1>{});
@@ -690,10 +835,9 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : 1)) void row_kernel(RowArgs A)
         if (A.topk_a_lq) A.topk_a_lq[t * k + r] = finite_row ? (float)dq : NaN;
     }
     // Membership of the policy list's ids in the actor list through a small open-addressing hash
-    // table (load factor <= 1/4) in the LDS pool, which is free by now.
-    constexpr int HT = 4 * KC;
-    static_assert(HT * 4 <= POOL_BYTES, "hash table must fit the pool");
-    uint32_t *const tab = (uint32_t *)pool;
+    // table (load factor <= 1/2) in the LDS pool, behind list 1.
+    constexpr int HT = 2 * KC;
+    uint32_t *const tab = (uint32_t *)pool + 3 * KC;
     lds_sync();
     for (int e = lane; e < HT; e += WAVE) tab[e] = 0xffffffffu;
     lds_sync();
