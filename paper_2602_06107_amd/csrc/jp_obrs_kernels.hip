@@ -46,8 +46,7 @@ __device__ __forceinline__ u32x4 stream_load(gvec_ptr p) { return __builtin_nont
 // Order-preserving map float -> uint32 (-0 is folded onto +0 so that equal values get equal keys).
 __device__ __forceinline__ uint32_t ord32(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    u = (u == 0x80000000u) ? 0u : u;
+    const uint32_t u = __float_as_uint(f + 0.0f);             // -0 + 0 = +0 (round to nearest)
     return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
 __device__ __forceinline__ float unord32(uint32_t o)
@@ -336,10 +335,9 @@ __device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typena
                                             float cmax, uint32_t c, bool pass, int k)
 {
     using Key = typename KT::Key;
-    if (__ballot(pass) == 0) return;
-    Key key = KT::make(cmax, c);
-    bool ins = pass && key >= st.tauk;
-    uint64_t bm = __ballot(ins);
+    const Key key = KT::make(cmax, c);
+    const bool ins = pass && key >= st.tauk;
+    const uint64_t bm = __ballot(ins);
     if (bm) {
         if (ins) buf[st.cnt + lane_prefix(bm)] = key;
         st.cnt += __popcll(bm);
@@ -351,15 +349,19 @@ __device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typena
             st.tauv = uniform_f(threshold_value<KT>(st.tauk));
         }
     }
-    if (__ballot(pass && cmax > st.mthr)) {
-        float wm = uniform_f(wave_max(pass ? cmax : neg_inf()));
-        float newM2 = wm * LOG2E_F;
-        const float rescale = __builtin_amdgcn_exp2f(st.M2 - newM2);
-        st.s *= rescale;
-        st.d *= rescale;
-        st.M2 = newM2;
-        st.mthr = wm + RESCALE_MARGIN2 / LOG2E_F;
-    }
+}
+
+// A chunk maximum above st.mthr moves the exponent reference of the stream.
+template <class Key>
+__device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, bool pass)
+{
+    const float wm = uniform_f(wave_max(pass ? cmax : neg_inf()));
+    const float newM2 = wm * LOG2E_F;
+    const float rescale = __builtin_amdgcn_exp2f(st.M2 - newM2);
+    st.s *= rescale;
+    st.d *= rescale;
+    st.M2 = newM2;
+    st.mthr = wm + RESCALE_MARGIN2 / LOG2E_F;
 }
 
 // log2 of a positive float sum: exponent plus hardware log2 of the mantissa in [1, 2), so the
@@ -544,9 +546,16 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
         const float mq = max_of<VEC>(fq), mp = max_of<VEC>(fp);
         const bool pq = valid && (mq >= sq.tauv);
         const bool pp = valid && (mp >= sp.tauv);
-        if (__ballot(pq || pp)) {
-            offer_chunk<KT, C, NS>(sq, s_desc0, mq, c, pq, k);
-            offer_chunk<KT, C, NS>(sp, s_desc1, mp, c, pp, k);
+        const uint64_t bq = __ballot(pq), bp = __ballot(pp);
+        if (bq | bp) {
+            if (bq) offer_chunk<KT, C, NS>(sq, s_desc0, mq, c, pq, k);
+            if (bp) offer_chunk<KT, C, NS>(sp, s_desc1, mp, c, pp, k);
+            // a value above the margin of an exponent reference is also above the top-k bound
+            const bool rq = pq && mq > sq.mthr, rp = pp && mp > sp.mthr;
+            if (__ballot(rq || rp)) {
+                if (__ballot(rq)) raise_reference(sq, mq, pq);
+                if (__ballot(rp)) raise_reference(sp, mp, pp);
+            }
         }
         sq.s += sum_exp2<VEC>(fq, sq.M2);
         if constexpr (DISTILL) sp.s += sum_exp2_kl<VEC>(fp, fq, sp.M2, sp.d);
