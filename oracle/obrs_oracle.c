@@ -257,6 +257,42 @@ int jpo_rows(const void *actor, const void *policy, int dtype, int64_t T, int64_
     return used;
 }
 
+/* ---- gradient of the distillation term (Sec. 4.2 (3), Eq. distill_loss) --
+ * The loss per token is KL(SG(p) || q) = sum_v p_v (log p_v - log q_v) with
+ * p held fixed, q = softmax(lq).  Since d log q_u / d lq_v = [u = v] - q_v,
+ *   d KL / d lq_v = -p_v + q_v sum_u p_u = q_v - p_v.
+ * out[v] = weight * (q_v - p_v).                                          */
+void jpo_distill_grad_row(const double *lq, const double *lp, int64_t V, double weight, double *out)
+{
+    const double lse_q = jpo_logsumexp(lq, V), lse_p = jpo_logsumexp(lp, V);
+    for (int64_t v = 0; v < V; ++v) out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));
+}
+
+/* The same for a batch stored in its input dtype.  Padding rows (x[t] < 0), rows whose
+ * sampled id is outside the vocabulary and rows with a non-finite log-sum-exp get zeros
+ * (they take no part in the loss).  weight_t = scale * (row_scale ? row_scale[t] : 1).  */
+void jpo_distill_grad(const void *actor, const void *policy, int dtype, int64_t T, int64_t V,
+                      int64_t row_stride, const int32_t *x, const float *row_scale, double scale,
+                      double *out /* [T, V] */)
+{
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    double *lq = (double *)malloc((size_t)V * sizeof(double));
+    double *lp = (double *)malloc((size_t)V * sizeof(double));
+    for (int64_t t = 0; t < T; ++t) {
+        double *o = out + (size_t)t * (size_t)V;
+        jpo_widen_row((const char *)actor + (size_t)t * (size_t)row_stride * esz, dtype, V, lq);
+        jpo_widen_row((const char *)policy + (size_t)t * (size_t)row_stride * esz, dtype, V, lp);
+        const double lse_q = jpo_logsumexp(lq, V), lse_p = jpo_logsumexp(lp, V);
+        if (x[t] < 0 || x[t] >= V || !isfinite(lse_q) || !isfinite(lse_p)) {
+            for (int64_t v = 0; v < V; ++v) o[v] = 0.0;
+            continue;
+        }
+        jpo_distill_grad_row(lq, lp, V, scale * (row_scale ? (double)row_scale[t] : 1.0), o);
+    }
+    free(lp);
+    free(lq);
+}
+
 /* ---- batch-level bias correction and weights (Sec. 4.4.2, Alg. 1 step 2-3)
  * mask[t] is taken as given (the Bernoulli draw is an input of this stage).
  * alpha_hat = accepted / proposed;  kappa = alpha_hat / mean(Z_approx);

@@ -85,6 +85,11 @@ def lib():
         l.jpo_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_double,
                                 C.c_double, C.c_void_p, C.c_int, C.POINTER(BatchOut),
                                 C.c_void_p, C.c_void_p]
+        l.jpo_distill_grad_row.restype = None
+        l.jpo_distill_grad_row.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_void_p]
+        l.jpo_distill_grad.restype = None
+        l.jpo_distill_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64,
+                                       C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         l.jpo_max_threads.restype = C.c_int
         l.jpo_widen_row.restype = None
         l.jpo_widen_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
@@ -182,6 +187,28 @@ def batch(rows_out: np.ndarray, mask, lam: float, c1: float, c2: float, ref_logp
     lib().jpo_batch(_ptr(rows_out), _ptr(mask), T, float(lam), float(c1), float(c2), _ptr(ref),
                     int(use_expected_alpha), C.byref(b), _ptr(w), _ptr(rho))
     return b, w, rho
+
+
+def distill_grad_row(lq, lp, weight: float = 1.0) -> np.ndarray:
+    """d KL(SG(p) || q) / d lq for one row (Sec. 4.2 (3)): weight * (q - p)."""
+    lq, lp = _f64(lq), _f64(lp)
+    out = np.empty_like(lq)
+    lib().jpo_distill_grad_row(_ptr(lq), _ptr(lp), lq.size, float(weight), _ptr(out))
+    return out
+
+
+def distill_grad(actor: np.ndarray, policy: np.ndarray, x, row_scale=None, scale: float = 1.0) -> np.ndarray:
+    """The same for a batch stored as float32 / float64 / bf16 bits; float64 [T, V]."""
+    assert actor.shape == policy.shape and actor.ndim == 2 and actor.dtype == policy.dtype
+    assert actor.strides[1] == actor.itemsize and policy.strides == actor.strides
+    a, code = storage_view(actor)
+    T, V = a.shape
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    rs = None if row_scale is None else np.ascontiguousarray(row_scale, dtype=np.float32)
+    out = np.empty((T, V), dtype=np.float64)
+    lib().jpo_distill_grad(_ptr(a), _ptr(policy), code, T, V, a.strides[0] // a.itemsize, _ptr(x),
+                           _ptr(rs), float(scale), _ptr(out))
+    return out
 
 
 def max_threads() -> int:

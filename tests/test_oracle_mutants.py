@@ -43,6 +43,12 @@ MUTANTS = [
      "rho *= rr < c2 ? rr : c2;", "rho *= rr > c2 ? rr : c2;"),
     ("KL(p||q) weights by q",
      "kl_pq += pv * (logp_v - logq_v);", "kl_pq += exp(logq_v) * (logp_v - logq_v);"),
+    ("distillation gradient has the wrong sign",
+     "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
+    ("distillation gradient drops the row weight",
+     "jpo_distill_grad_row(lq, lp, V, scale * (row_scale ? (double)row_scale[t] : 1.0), o);", "jpo_distill_grad_row(lq, lp, V, scale, o);"),
+    ("distillation gradient fills padding rows",
+     "if (x[t] < 0 || x[t] >= V || !isfinite(lse_q) || !isfinite(lse_p)) {", "if (x[t] >= V || !isfinite(lse_q) || !isfinite(lse_p)) {"),
 ]
 
 

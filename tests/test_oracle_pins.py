@@ -430,3 +430,56 @@ def test_distillation_kl_against_scipy_rel_entr_and_batch_mean():
     # KL is not symmetric: swapping the roles of the two rows changes the value
     out_sw, _, _ = orc.row(lp, lq, 0, 0.5, 1.0, 4)
     assert abs(out_sw.kl_p_q - outs[3].kl_p_q) > 1e-3
+
+
+# ---- gradient of the distillation term w.r.t. the actor logits: q - p ------------------------------
+
+def test_distillation_gradient_against_finite_differences():
+    rng = np.random.default_rng(222)
+    V = 40
+    lq = _rand_logits(rng, V)
+    lp = lq + rng.normal(0, 1.0, V)
+    p = _softmax64(lp)
+
+    def kl_of(lq_):                                   # scipy only: no oracle call in the expected value
+        return float(scipy.special.rel_entr(p, _softmax64(lq_)).sum())
+
+    g = orc.distill_grad_row(lq, lp, 1.0)
+    h = 1e-5
+    for v in range(V):
+        e = np.zeros(V)
+        e[v] = h
+        fd = (kl_of(lq + e) - kl_of(lq - e)) / (2 * h)
+        assert g[v] == pytest.approx(fd, abs=2e-9)
+    assert abs(g.sum()) < 1e-14                       # softmax gradients sum to zero
+    np.testing.assert_allclose(orc.distill_grad_row(lq, lp, -2.5), -2.5 * g, rtol=1e-14, atol=0)
+    np.testing.assert_array_equal(orc.distill_grad_row(lq, lq, 1.0), np.zeros(V))   # p == q
+    # two tokens, closed form: q = (s(a), 1 - s(a)), p = (s(b), 1 - s(b)) with the logistic function s
+    a, b = 0.7, -1.1
+    g2 = orc.distill_grad_row([a, 0.0], [b, 0.0], 1.0)
+    s = lambda z: 1.0 / (1.0 + math.exp(-z))
+    assert g2[0] == pytest.approx(s(a) - s(b), rel=1e-14)
+    assert g2[1] == pytest.approx(s(b) - s(a), rel=1e-14)
+
+
+def test_distillation_gradient_batch_driver():
+    rng = np.random.default_rng(223)
+    T, V = 5, 33
+    a32 = rng.normal(0, 2, (T, V)).astype(np.float32)
+    p32 = (a32 + rng.normal(0, 1, (T, V))).astype(np.float32)
+    x = np.array([3, -1, 0, V, 7], dtype=np.int32)    # row 1 padding, row 3 id out of range
+    rs = np.array([1.0, 2.0, 0.5, 1.0, -1.5], dtype=np.float32)
+    G = orc.distill_grad(a32, p32, x, rs, scale=0.25)
+    for t in range(T):
+        if x[t] < 0 or x[t] >= V:
+            np.testing.assert_array_equal(G[t], np.zeros(V))
+        else:
+            want = 0.25 * float(rs[t]) * (_softmax64(a32[t]) - _softmax64(p32[t]))
+            np.testing.assert_allclose(G[t], want, rtol=1e-12, atol=1e-16)
+    # bf16 storage is widened exactly
+    abits = (a32.view(np.uint32) >> 16).astype(np.uint16)
+    pbits = (p32.view(np.uint32) >> 16).astype(np.uint16)
+    Gb = orc.distill_grad(abits, pbits, x)
+    a_w = (abits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    p_w = (pbits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    np.testing.assert_allclose(Gb[0], _softmax64(a_w[0]) - _softmax64(p_w[0]), rtol=1e-12, atol=1e-16)
