@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
                          "a kernel of known HBM traffic that scales rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--grad", choices=["none", "bf16", "f32"], default="none",
+                    help="also time jp_obrs_distill_grad (gradient of the distillation term w.r.t. the "
+                         "actor logits, written in this dtype) and report it as \"distill_grad\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -157,6 +160,26 @@ def main():
     achieved = algo_bytes / (row_ms_avg * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get((T, V, w.k))
 
+    grad_info = None
+    if args.grad != "none":
+        gdt = torch.bfloat16 if args.grad == "bf16" else torch.float32
+        grad = torch.empty((T, V), dtype=gdt, device=dev)
+        gev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps + 1)]
+        for a, b in gev:
+            a.record()
+            obrs.jp_obrs_distill_grad(w.actor, w.policy, None, 1.0 / T, grad, buf)
+            b.record()
+        torch.cuda.synchronize()
+        g_ms = sorted(a.elapsed_time(b) for a, b in gev[1:])
+        g_avg = sum(g_ms) / len(g_ms)
+        g_bytes = T * (V * (2 * esz + grad.element_size()) + 8 + 8 + 1)   # two rows in, one row out, LSEs, row status
+        grad_info = {"kernel": "distill_grad_kernel<bf16,%s>" % args.grad, "kernel_ms_avg": g_avg,
+                     "kernel_ms_min": g_ms[0], "algorithmic_bytes": g_bytes, "bound": "hbm",
+                     "achieved": g_bytes / (g_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": g_bytes / (g_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "tokens_per_s": T / (g_avg * 1e-3)}
+        del grad
+
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)
         for _ in range(args.calibrate_copy):
@@ -205,6 +228,8 @@ def main():
                      "kernel_ms_min": row_ms[0], "algorithmic_bytes": algo_bytes},
         "cpu_baseline": cpu,
     }
+    if grad_info is not None:
+        line["distill_grad"] = grad_info
     print(json.dumps(line), flush=True)
 
 

@@ -170,6 +170,27 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
                                  const jp_obrs_outputs *out, void *workspace,
                                  size_t workspace_bytes, void *stream);
 
+/*
+ * Gradient of the on-policy distillation term of Sec. 4.2 (3), Eq. distill_loss, with respect to
+ * the actor logits.  The term per token is KL(SG(p_t) || q_t) with the target p_t held fixed and
+ * q_t = softmax(actor logits), so d/d lq_t[v] = q_t(v) - p_t(v).  This call writes
+ *   grad_actor[t, v] = scale * (row_scale ? row_scale[t] : 1) * (q_t(v) - p_t(v))
+ * (e.g. scale = lambda_distill / B for the batch mean of the joint objective, Eq. sys_joint_obj).
+ * It is a second streaming pass over the two logit tensors that takes the two log-sum-exps and the
+ * row status from `workspace`, where a preceding jp_obrs_rows / jp_obrs_forward call on the SAME
+ * tensors, T and workspace left them.  Rows that were padding, had a sampled id outside the
+ * vocabulary or a non-finite log-sum-exp get zeros.
+ *   grad_actor: device [T, V], grad_row_stride elements between rows (>= V), dtype grad_dt
+ *               (JP_F32, or JP_BF16 rounded to nearest even); 16-byte aligned base and row pitch.
+ *   row_scale:  device [T] or NULL.
+ * Status codes as for jp_obrs_forward; scale must be finite.  Nothing else is read or written.
+ */
+jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logits,
+                               int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                               const float *row_scale, float scale,
+                               void *grad_actor, int64_t grad_row_stride, jp_dtype grad_dt,
+                               const void *workspace, size_t workspace_bytes, void *stream);
+
 const char *jp_status_string(jp_status s);
 
 /* ABI version of this header (bumped on incompatible change). */

@@ -289,6 +289,34 @@ jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits, i
                          (hipStream_t)stream, uniforms != nullptr);
 }
 
+/* Gradient of the distillation term with respect to the actor logits (second streaming pass). */
+jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
+                               int64_t row_stride, jp_dtype dt, const float *row_scale, float scale,
+                               void *grad_actor, int64_t grad_row_stride, jp_dtype grad_dt,
+                               const void *workspace, size_t workspace_bytes, void *stream)
+{
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s != JP_OK) return s;
+    if (grad_dt != JP_F32 && grad_dt != JP_BF16) return JP_ERR_UNSUPPORTED;
+    if (grad_row_stride < V) return JP_ERR_SHAPE;
+    if (!isfinite(scale)) return JP_ERR_PARAM;
+    if (T > 0 && (!actor_logits || !policy_logits || !grad_actor)) return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4, gsz = grad_dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(actor_logits) || !aligned16(policy_logits) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    if (!aligned16(grad_actor) || ((size_t)grad_row_stride * gsz) % 16 != 0) return JP_ERR_ALIGN;
+    const Workspace w = carve(const_cast<void *>(workspace), T);
+    if (!workspace || workspace_bytes < w.bytes) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+    if (T == 0) return JP_OK;
+    jp::GradArgs g{};
+    g.actor = actor_logits; g.policy = policy_logits; g.T = T; g.V = V; g.stride = row_stride;
+    g.lse_q = w.lse_q; g.lse_p = w.lse_p; g.rowflag = w.rowflag;
+    g.row_scale = row_scale; g.scale = scale;
+    g.grad = grad_actor; g.grad_stride = grad_row_stride;
+    if (jp::launch_distill_grad(g, (int)dt, (int)grad_dt, (hipStream_t)stream) != hipSuccess) return JP_ERR_HIP;
+    return JP_OK;
+}
+
 const char *jp_status_string(jp_status s)
 {
     switch (s) {
@@ -304,6 +332,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 2; }
+int jp_obrs_abi_version(void) { return 3; }
 
 }  // extern "C"

@@ -71,7 +71,20 @@ struct FinalizeArgs {
     float *w, *rho;
 };
 
+struct GradArgs {
+    const void *actor, *policy;       // [T, V] logits, `stride` elements between rows
+    int64_t T, V, stride;
+    const double *lse_q, *lse_p;      // [T] from the row stage
+    const uint8_t *rowflag;           // [T] from the row stage
+    const float *row_scale;           // [T] or nullptr
+    float scale;
+    void *grad;                       // [T, V], `grad_stride` elements between rows
+    int64_t grad_stride;
+    uint32_t seg_batches, segs;       // set by the launcher: batches of 1024 chunks per workgroup, workgroups per row
+};
+
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
+hipError_t launch_distill_grad(const GradArgs &a, int dtype, int grad_dtype, hipStream_t st);
 // Two independent TN GEMMs sharing M, N and ldc (policy head and actor head of one vocabulary chunk).
 struct GemmArgs {
     const void *A[2];                 // [M, K] bf16

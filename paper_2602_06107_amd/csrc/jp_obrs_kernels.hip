@@ -938,6 +938,115 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
 }
 
 // =================================================================================================
+// Gradient of the distillation term KL(SG(p) || q) of Sec. 4.2 (3) with respect to the actor
+// logits: g_t[v] = w_t (q_t(v) - p_t(v)), q = 2^(lq log2e - LSEq log2e), p likewise.  A second
+// streaming pass: reads both logit rows once, writes one row.  A workgroup of 256 threads covers
+// GRAD_CHUNKS 16-byte chunks per thread of one row; the loads of a thread are issued together.
+// =================================================================================================
+constexpr int GRAD_THREADS = 256;
+constexpr int GRAD_CHUNKS = 4;
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)     // round to nearest even
+{
+    const bf16x2_t r = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, r);
+}
+struct Bf16Out {
+    static constexpr int ESZ = 2;
+    static __device__ __forceinline__ void store1(char *row, int64_t i, float v)
+    {
+        ((uint16_t *)row)[i] = (uint16_t)pack_bf16x2(v, 0.f);
+    }
+    template <int VEC> static __device__ __forceinline__ void store(char *row, uint32_t c, const float (&g)[VEC])
+    {
+        uint32_t w[VEC / 2];
+#pragma unroll
+        for (int j = 0; j < VEC / 2; ++j) w[j] = pack_bf16x2(g[2 * j], g[2 * j + 1]);
+        // written once, not read again by this pass: non-temporal stores
+        if constexpr (VEC == 8) __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, (u32x4 *)row + c);
+        else __builtin_nontemporal_store(((uint64_t)w[1] << 32) | w[0], (uint64_t *)row + c);
+    }
+};
+struct F32Out {
+    static constexpr int ESZ = 4;
+    static __device__ __forceinline__ void store1(char *row, int64_t i, float v) { ((float *)row)[i] = v; }
+    template <int VEC> static __device__ __forceinline__ void store(char *row, uint32_t c, const float (&g)[VEC])
+    {
+#pragma unroll
+        for (int j = 0; j < VEC / 4; ++j)
+            __builtin_nontemporal_store(u32x4{__float_as_uint(g[4 * j]), __float_as_uint(g[4 * j + 1]),
+                                              __float_as_uint(g[4 * j + 2]), __float_as_uint(g[4 * j + 3])},
+                                        (u32x4 *)row + ((size_t)c * (VEC / 4) + j));
+    }
+};
+
+template <class ET, class OT>
+__global__ __launch_bounds__(GRAD_THREADS) void distill_grad_kernel(GradArgs A)
+{
+    constexpr int VEC = ET::VEC;
+    // one-dimensional launch, segments of a row adjacent: consecutive workgroups stream consecutive memory
+    const int64_t t = blockIdx.x / A.segs;
+    const uint32_t seg = blockIdx.x - (uint32_t)t * A.segs;
+    const int64_t V = A.V;
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    char *rowg = (char *)A.grad + (size_t)t * (size_t)A.grad_stride * OT::ESZ;
+    // This workgroup covers chunks [seg_begin, seg_end) of the row in batches of GRAD_CHUNKS chunks
+    // per thread; the loads of the next batch are issued before the current one is computed, and
+    // the first batch is requested before the row constants are read.
+    const uint32_t seg_len = A.seg_batches * (GRAD_THREADS * GRAD_CHUNKS);
+    const uint32_t seg_begin = seg * seg_len;
+    const uint32_t seg_end = seg_begin + seg_len < nfull ? seg_begin + seg_len : nfull;
+    u32x4 rq[GRAD_CHUNKS], rp[GRAD_CHUNKS];
+    auto request = [&](uint32_t base) {
+#pragma unroll
+        for (int u = 0; u < GRAD_CHUNKS; ++u) {
+            uint32_t c = base + u * GRAD_THREADS + threadIdx.x;
+            c = c < seg_end ? c : (seg_end > 0 ? seg_end - 1 : 0);   // clamp: a harmless repeat, never stored
+            rq[u] = stream_load(as_global_vec(rowq) + c);
+            rp[u] = stream_load(as_global_vec(rowp) + c);
+        }
+    };
+    if (seg_begin < seg_end) request(seg_begin);
+    const bool live = A.rowflag[t] == ROW_OK;
+    const float w = live ? A.scale * (A.row_scale ? A.row_scale[t] : 1.f) : 0.f;
+    const float Aq = live ? (float)(A.lse_q[t] * LOG2E_D) : 0.f;
+    const float Ap = live ? (float)(A.lse_p[t] * LOG2E_D) : 0.f;
+    auto grad_of = [&](float lq, float lp) {
+        const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(lq, LOG2E_F, -Aq));
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(lp, LOG2E_F, -Ap));
+        return live ? w * (q - p) : 0.f;               // rows outside the loss get exact zeros
+    };
+    for (uint32_t base = seg_begin; base < seg_end; base += GRAD_THREADS * GRAD_CHUNKS) {
+        u32x4 cq[GRAD_CHUNKS], cp[GRAD_CHUNKS];
+#pragma unroll
+        for (int u = 0; u < GRAD_CHUNKS; ++u) { cq[u] = rq[u]; cp[u] = rp[u]; }
+        if (base + GRAD_THREADS * GRAD_CHUNKS < seg_end) request(base + GRAD_THREADS * GRAD_CHUNKS);
+#pragma unroll
+        for (int u = 0; u < GRAD_CHUNKS; ++u) {
+            const uint32_t c = base + u * GRAD_THREADS + threadIdx.x;
+            if (c < seg_end) {
+                float fq[VEC], fp[VEC], g[VEC];
+                ET::unpack(cq[u], fq);
+                ET::unpack(cp[u], fp);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) g[j] = grad_of(fq[j], fp[j]);
+                OT::template store<VEC>(rowg, c, g);
+            }
+        }
+    }
+    // the ragged end of the row, element by element
+    if (seg == 0 && (int)threadIdx.x < tail) {
+        const int64_t i = (int64_t)nfull * VEC + threadIdx.x;
+        OT::store1(rowg, i, grad_of(ET::load1(rowq, i), ET::load1(rowp, i)));
+    }
+}
+
+// =================================================================================================
 // Batch stage (Sec. 4.4.2 and Alg. 1 step 3) in one launch.  Every workgroup sums the whole batch
 // in the same fixed order (per-thread strided sums, wave butterflies, then the 16 wave partials in
 // index order), so all workgroups hold bit-identical statistics, run to run as well; each then
@@ -1115,6 +1224,35 @@ hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
     int64_t blocks = (a.T + FINALIZE_THREADS - 1) / FINALIZE_THREADS;
     blocks = blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)blocks), dim3(FINALIZE_THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_distill_grad(const GradArgs &a, int dtype, int grad_dtype, hipStream_t st)
+{
+    const int vec = dtype == JP_BF16 ? 8 : 4;
+    const int64_t nfull = a.V / vec;
+    const int64_t per_batch = (int64_t)GRAD_THREADS * GRAD_CHUNKS;
+    const int64_t batches = nfull > 0 ? (nfull + per_batch - 1) / per_batch : 1;
+    // long enough segments to amortise the row constants, short enough to fill the chip at small T
+    int64_t seg_batches = a.T >= 4096 ? 5 : (a.T >= 512 ? 2 : 1);
+    if (seg_batches > batches) seg_batches = batches;
+    int64_t segs = (batches + seg_batches - 1) / seg_batches;
+    while (segs * a.T > 0x7fffffffLL) {                       // grid.x limit: longer segments
+        seg_batches *= 2;
+        segs = (batches + seg_batches - 1) / seg_batches;
+    }
+    GradArgs g = a;
+    g.seg_batches = (uint32_t)seg_batches;
+    g.segs = (uint32_t)segs;
+    const dim3 grid((unsigned)(a.T * segs));
+    if (dtype == JP_BF16 && grad_dtype == JP_BF16)
+        hipLaunchKernelGGL((distill_grad_kernel<Bf16Elem, Bf16Out>), grid, dim3(GRAD_THREADS), 0, st, g);
+    else if (dtype == JP_BF16)
+        hipLaunchKernelGGL((distill_grad_kernel<Bf16Elem, F32Out>), grid, dim3(GRAD_THREADS), 0, st, g);
+    else if (grad_dtype == JP_BF16)
+        hipLaunchKernelGGL((distill_grad_kernel<F32Elem, Bf16Out>), grid, dim3(GRAD_THREADS), 0, st, g);
+    else
+        hipLaunchKernelGGL((distill_grad_kernel<F32Elem, F32Out>), grid, dim3(GRAD_THREADS), 0, st, g);
     return hipGetLastError();
 }
 

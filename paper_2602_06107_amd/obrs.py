@@ -24,7 +24,7 @@ JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
  JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
 
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
-           "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead",
+           "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -75,6 +75,10 @@ _lib.jp_obrs_forward_lmhead.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_v
                                         C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(Params), C.POINTER(Outputs), C.c_void_p, C.c_size_t,
                                         C.c_void_p]
+_lib.jp_obrs_distill_grad.restype = C.c_int
+_lib.jp_obrs_distill_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                      C.c_void_p, C.c_float, C.c_void_p, C.c_int64, C.c_int,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -188,6 +192,20 @@ def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c
     st = _lib.jp_obrs_forward(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
                               _p(ref_logprob), C.byref(prm), C.byref(buf.out), _p(buf.workspace),
                               buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_distill_grad(actor, policy, row_scale, scale, grad, buf: Buffers, stream=None) -> None:
+    """grad[t, v] = scale * row_scale[t] * (q_t(v) - p_t(v)) from the log-sum-exps that a preceding
+    jp_obrs_rows / jp_obrs_forward call left in ``buf.workspace``."""
+    T, V, stride, dt = _logit_args(actor, policy)
+    if grad.dim() != 2 or tuple(grad.shape) != (T, V) or grad.stride(1) != 1:
+        raise ValueError("grad must be a [T, V] tensor with contiguous rows")
+    gstride = grad.stride(0) if T > 1 else max(grad.stride(0), V)
+    st = _lib.jp_obrs_distill_grad(_p(actor), _p(policy), T, V, stride, dt, _p(row_scale), float(scale),
+                                   _p(grad), gstride, _dtype_code(grad), _p(buf.workspace),
+                                   buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 
