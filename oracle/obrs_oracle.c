@@ -205,6 +205,128 @@ void jpo_row(const double *lq, const double *lp, int64_t V, int32_t x, double u,
     free(kq);
 }
 
+/* ---- one token position with the actor side as the rollout phase stored it --------------
+ * Alg. 1, Phase 1 keeps, per position, the sampled token's probability p_inf(a_t) and the top-k
+ * log-probabilities TopK_inf of the rollout model, not its logits; Phase 2 has the target
+ * model's full logits.  So here: lp[V] target logits; ids_q[nq], logq_ids[nq] the stored list
+ * (an id < 0 marks an unused slot, a repeated id counts once); logq_x = log q(x).
+ *   a(x), mask: as in jpo_row, from logq_x and log p(x).
+ *   V_k = stored ids U top-k(p)                                     (Alg. 1 step 2)
+ *   Z_approx = sum_{v in stored} min(q_v, p_v/lambda) + sum_{v in top-k(p), not stored} min(qhat, p_v/lambda)
+ * The paper does not say what q_v is for a token of TopK_new that TopK_inf does not hold.  qhat is
+ * a stated rule: 0 = such tokens contribute nothing; 1 = the smallest stored probability (an
+ * upper bound of q_v, since v is not among the k largest); 2 = the probability mass the stored
+ * list leaves, spread evenly over the other V - n tokens, capped by rule 1's bound.
+ * z_exact, kl_* are not available in this form (NaN).                                         */
+enum { JPO_TAIL_DROP = 0, JPO_TAIL_KTH = 1, JPO_TAIL_REST = 2 };
+
+void jpo_row_stored(const double *lp, int64_t V, const int32_t *ids_q, const double *logq_ids,
+                    int32_t nq, double logq_x, int32_t x, double u, double lambda, int32_t k,
+                    int tail_rule, jpo_row_out *out, int32_t *topk_p)
+{
+    memset(out, 0, sizeof *out);
+    if (x < 0) return;
+    out->valid = 1;
+    double lse_p = jpo_logsumexp(lp, V);
+    out->lse_q = 0.0;
+    out->lse_p = lse_p;
+    out->logq_x = logq_x;
+    out->logp_x = lp[x] - lse_p;
+    out->logratio = out->logp_x - out->logq_x;
+    double r = exp(out->logratio) / lambda;
+    out->accept = r < 1.0 ? r : 1.0;
+    out->mask = (u < out->accept) ? 1 : 0;
+
+    /* the stored list: first occurrence of every valid id */
+    double *qlog = (double *)malloc((size_t)V * sizeof(double));
+    unsigned char *stored = (unsigned char *)calloc((size_t)V, 1);
+    int64_t n = 0;
+    double kth = 0.0, mass = 0.0;          /* smallest stored log-probability, stored probability mass */
+    for (int32_t j = 0; j < nq; ++j) {
+        int32_t v = ids_q[j];
+        if (v < 0 || v >= V || stored[v]) continue;
+        stored[v] = 1;
+        qlog[v] = logq_ids[j];
+        if (n == 0 || logq_ids[j] < kth) kth = logq_ids[j];
+        mass += exp(logq_ids[j]);
+        ++n;
+    }
+    double tail;                            /* log qhat */
+    if (tail_rule == JPO_TAIL_DROP || n == V) {
+        tail = -INFINITY;
+    } else if (tail_rule == JPO_TAIL_KTH) {
+        tail = kth;                         /* log 1 = 0 when nothing is stored */
+    } else {
+        double rest = 1.0 - mass;
+        if (rest < 0.0) rest = 0.0;
+        double share = rest / (double)(V - n);
+        tail = log(share);
+        if (tail > kth) tail = kth;
+    }
+
+    int32_t *kp = (int32_t *)malloc((size_t)k * sizeof(int32_t));
+    jpo_topk(lp, V, k, kp);
+    unsigned char *in_p = (unsigned char *)calloc((size_t)V, 1);
+    for (int32_t j = 0; j < k; ++j) in_p[kp[j]] = 1;
+    double z = 0.0;
+    int32_t usize = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (stored[v]) {
+            z += kept_mass(qlog[v], lp[v] - lse_p, lambda);
+            ++usize;
+        } else if (in_p[v]) {
+            z += kept_mass(tail, lp[v] - lse_p, lambda);
+            ++usize;
+        }
+    }
+    out->z_approx = z;
+    out->union_size = usize;
+    out->z_exact = NAN;
+    out->kl_p_q = NAN;
+    out->kl_p_qtilde = NAN;
+    if (topk_p) memcpy(topk_p, kp, (size_t)k * sizeof(int32_t));
+    free(in_p);
+    free(kp);
+    free(stored);
+    free(qlog);
+}
+
+/* The same for a batch: target logits in their storage dtype, the stored actor side as the
+ * rollout phase would hand it over (int32 ids, float32 log-probabilities).  Returns threads used. */
+int jpo_rows_stored(const void *policy, int dtype, int64_t T, int64_t V, int64_t row_stride,
+                    const int32_t *ids_q, const float *logq_ids, const float *logq_x,
+                    const int32_t *x, const float *u, double lambda, int32_t k, int tail_rule,
+                    jpo_row_out *out, int32_t *topk_p, int n_threads)
+{
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+#else
+    {
+#endif
+        double *lp = (double *)malloc((size_t)V * sizeof(double));
+        double *lq = (double *)malloc((size_t)k * sizeof(double));
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t t = 0; t < T; ++t) {
+            jpo_widen_row((const char *)policy + (size_t)t * (size_t)row_stride * esz, dtype, V, lp);
+            for (int32_t j = 0; j < k; ++j) lq[j] = (double)logq_ids[(size_t)t * k + j];
+            jpo_row_stored(lp, V, ids_q + (size_t)t * k, lq, k, (double)logq_x[t], x[t],
+                           u ? (double)u[t] : 2.0, lambda, k, tail_rule, &out[t],
+                           topk_p ? topk_p + (size_t)t * k : NULL);
+        }
+        free(lq);
+        free(lp);
+    }
+    return used;
+}
+
 /* Post-rejection distribution q~_v = min(q_v, p_v/lambda) / Z for one row
  * (Eq. obrs_dist), written to qt[V]; returns Z. */
 double jpo_post_rejection(const double *lq, const double *lp, int64_t V, double lambda, double *qt)

@@ -90,6 +90,14 @@ def lib():
         l.jpo_distill_grad.restype = None
         l.jpo_distill_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64,
                                        C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
+        l.jpo_row_stored.restype = None
+        l.jpo_row_stored.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_double,
+                                     C.c_int32, C.c_double, C.c_double, C.c_int32, C.c_int,
+                                     C.POINTER(RowOut), C.c_void_p]
+        l.jpo_rows_stored.restype = C.c_int
+        l.jpo_rows_stored.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
+                                      C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int]
         l.jpo_max_threads.restype = C.c_int
         l.jpo_widen_row.restype = None
         l.jpo_widen_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
@@ -209,6 +217,43 @@ def distill_grad(actor: np.ndarray, policy: np.ndarray, x, row_scale=None, scale
     lib().jpo_distill_grad(_ptr(a), _ptr(policy), code, T, V, a.strides[0] // a.itemsize, _ptr(x),
                            _ptr(rs), float(scale), _ptr(out))
     return out
+
+
+TAIL_DROP, TAIL_KTH, TAIL_REST = 0, 1, 2
+
+
+def row_stored(lp, ids_q, logq_ids, logq_x: float, x: int, u: float, lam: float, k: int, tail_rule: int):
+    """One token position with the actor side as stored by the rollout phase (Alg. 1, Phase 1):
+    -> (RowOut, topk_p ids)."""
+    lp = _f64(lp)
+    ids = np.ascontiguousarray(ids_q, dtype=np.int32)
+    lq = _f64(logq_ids)
+    assert ids.shape == lq.shape and ids.ndim == 1
+    out = RowOut()
+    kp = np.empty(k, dtype=np.int32)
+    lib().jpo_row_stored(_ptr(lp), lp.size, _ptr(ids), _ptr(lq), ids.size, float(logq_x), int(x),
+                         float(u), float(lam), int(k), int(tail_rule), C.byref(out), _ptr(kp))
+    return out, kp
+
+
+def rows_stored(policy: np.ndarray, ids_q, logq_ids, logq_x, x, u, lam: float, k: int, tail_rule: int,
+                n_threads: int = 0) -> Rows:
+    """All rows of a batch in the stored-actor form; ``topk_q`` of the result is the stored id list."""
+    assert policy.ndim == 2 and policy.strides[1] == policy.itemsize
+    a, code = storage_view(policy)
+    T, V = a.shape
+    ids = np.ascontiguousarray(ids_q, dtype=np.int32)
+    lq = np.ascontiguousarray(logq_ids, dtype=np.float32)
+    assert ids.shape == (T, k) and lq.shape == (T, k)
+    lqx = np.ascontiguousarray(logq_x, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    uu = None if u is None else np.ascontiguousarray(u, dtype=np.float32)
+    out = np.zeros(T, dtype=ROW_DTYPE)
+    kp = np.empty((T, k), dtype=np.int32)
+    used = lib().jpo_rows_stored(_ptr(a), code, T, V, a.strides[0] // a.itemsize, _ptr(ids), _ptr(lq),
+                                 _ptr(lqx), _ptr(x), _ptr(uu), float(lam), int(k), int(tail_rule),
+                                 _ptr(out), _ptr(kp), int(n_threads))
+    return Rows(out, ids, kp, used)
 
 
 def max_threads() -> int:

@@ -43,6 +43,14 @@ MUTANTS = [
      "rho *= rr < c2 ? rr : c2;", "rho *= rr > c2 ? rr : c2;"),
     ("KL(p||q) weights by q",
      "kl_pq += pv * (logp_v - logq_v);", "kl_pq += exp(logq_v) * (logp_v - logq_v);"),
+    ("stored form: the k-th bound takes the largest stored value",
+     "if (n == 0 || logq_ids[j] < kth) kth = logq_ids[j];", "if (n == 0 || logq_ids[j] > kth) kth = logq_ids[j];"),
+    ("stored form: a repeated id is counted twice",
+     "if (v < 0 || v >= V || stored[v]) continue;", "if (v < 0 || v >= V) continue;"),
+    ("stored form: the even share ignores the stored mass",
+     "double rest = 1.0 - mass;", "double rest = 1.0;"),
+    ("stored form: tokens of TopK_new outside the stored list are dropped under every rule",
+     "z += kept_mass(tail, lp[v] - lse_p, lambda);\n            ++usize;", "++usize;"),
     ("distillation gradient has the wrong sign",
      "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
     ("distillation gradient drops the row weight",

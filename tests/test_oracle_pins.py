@@ -483,3 +483,109 @@ def test_distillation_gradient_batch_driver():
     a_w = (abits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
     p_w = (pbits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
     np.testing.assert_allclose(Gb[0], _softmax64(a_w[0]) - _softmax64(p_w[0]), rtol=1e-12, atol=1e-16)
+
+
+# ---- stored-actor form (Alg. 1: Phase 1 keeps TopK_inf log-probabilities and p_inf(a_t)) ------------
+
+def _stable_topk(l, k):
+    return np.argsort(-np.asarray(l), kind="stable")[:k]
+
+
+def _z_stored_numpy(lp, ids_q, logq_ids, lam, k, rule):
+    """Z_approx of the stored form written out with numpy sets (no oracle call)."""
+    V = lp.size
+    p = _softmax64(lp)
+    q_of = {}
+    for v, lq in zip(ids_q, logq_ids):
+        if 0 <= v < V and v not in q_of:
+            q_of[int(v)] = math.exp(lq)
+    n = len(q_of)
+    kth = min(q_of.values()) if n else 1.0
+    if rule == 0 or n == V:
+        qhat = 0.0
+    elif rule == 1:
+        qhat = kth
+    else:
+        qhat = min(kth, max(0.0, 1.0 - sum(q_of.values())) / (V - n))
+    z = sum(min(qv, p[v] / lam) for v, qv in q_of.items())
+    extra = [int(v) for v in _stable_topk(lp, k) if int(v) not in q_of]
+    z += sum(min(qhat, p[v] / lam) for v in extra)
+    return z, n + len(extra)
+
+
+@pytest.mark.parametrize("rule", [0, 1, 2])
+def test_stored_actor_form_against_numpy_sets(rule):
+    rng = np.random.default_rng(333 + rule)
+    for V, k, lam in ((50, 5, 1.0), (200, 16, 0.6), (64, 64, 2.0), (300, 20, 1.3)):
+        lq = _rand_logits(rng, V)
+        lp = lq + rng.normal(0, 1.0, V)
+        logq = lq - scipy.special.logsumexp(lq)
+        ids_q = _stable_topk(lq, k)
+        x = int(rng.integers(V))
+        u = float(rng.random())
+        out, kp = orc.row_stored(lp, ids_q, logq[ids_q], logq[x], x, u, lam, k, rule)
+        z, usize = _z_stored_numpy(lp, ids_q, logq[ids_q], lam, k, rule)
+        assert out.z_approx == pytest.approx(z, rel=1e-12)
+        assert out.union_size == usize
+        np.testing.assert_array_equal(kp, _stable_topk(lp, k))
+        logp = lp - scipy.special.logsumexp(lp)
+        assert out.logratio == pytest.approx(logp[x] - logq[x], abs=1e-12)
+        assert out.accept == pytest.approx(min(1.0, math.exp(logp[x] - logq[x]) / lam), rel=1e-12)
+        assert out.mask == (1 if u < out.accept else 0)
+        assert math.isnan(out.z_exact)
+
+
+def test_stored_actor_form_brackets_and_reduces_to_the_full_form():
+    rng = np.random.default_rng(337)
+    V, k, lam = 400, 24, 1.1
+    lq = _rand_logits(rng, V)
+    lp = lq + rng.normal(0, 1.5, V)
+    logq = lq - scipy.special.logsumexp(lq)
+    ids_q = _stable_topk(lq, k)
+    full, kq_full, _ = orc.row(lq, lp, 7, 0.5, lam, k)
+    np.testing.assert_array_equal(kq_full, ids_q)
+    z = [orc.row_stored(lp, ids_q, logq[ids_q], logq[7], 7, 0.5, lam, k, r)[0].z_approx for r in (0, 1, 2)]
+    # dropping the unknown terms under-estimates, the k-th-value bound over-estimates the estimate
+    # made with the true q; the even share of the remaining mass lies between the two
+    assert z[0] <= full.z_approx + 1e-15 <= z[1] + 2e-15
+    assert z[0] <= z[2] <= z[1]
+    assert z[0] < z[1]                                         # the lists differ for this seed
+    assert full.union_size == orc.row_stored(lp, ids_q, logq[ids_q], logq[7], 7, 0.5, lam, k, 1)[0].union_size
+    # with the whole vocabulary stored nothing is unknown: every rule gives the full form's value
+    allv = np.arange(V)
+    fullV, _, _ = orc.row(lq, lp, 7, 0.5, lam, V)
+    for r in (0, 1, 2):
+        o, _ = orc.row_stored(lp, allv, logq, logq[7], 7, 0.5, lam, V, r)
+        assert o.z_approx == pytest.approx(fullV.z_approx, rel=1e-13)
+        assert o.z_approx == pytest.approx(fullV.z_exact, rel=1e-13)
+    # p == q and lambda <= 1: acceptance 1; the estimate is the stored mass (+ nothing new in TopK_new)
+    o, _ = orc.row_stored(lq, ids_q, logq[ids_q], logq[7], 7, 0.99, 1.0, k, 1)
+    assert o.accept == 1.0 and o.mask == 1
+    assert o.z_approx == pytest.approx(np.exp(logq[ids_q]).sum(), rel=1e-13)
+    assert o.union_size == k
+
+
+def test_stored_actor_form_unused_slots_duplicates_and_batch_driver():
+    rng = np.random.default_rng(339)
+    T, V, k = 6, 120, 8
+    pol = rng.normal(0, 2, (T, V)).astype(np.float32)
+    act = (pol + rng.normal(0, 1, (T, V))).astype(np.float64)
+    logq = act - scipy.special.logsumexp(act, axis=1, keepdims=True)
+    ids = np.stack([_stable_topk(act[t], k) for t in range(T)]).astype(np.int32)
+    lq_ids = np.take_along_axis(logq, ids, axis=1).astype(np.float32)
+    ids[1, 3] = -1                                            # an unused slot
+    ids[3, 5] = ids[3, 0]                                     # a repeated id counts once
+    x = np.array([3, 5, -1, 9, 0, 11], dtype=np.int32)         # row 2 is padding
+    lqx = logq[np.arange(T), np.maximum(x, 0)].astype(np.float32)
+    u = rng.random(T).astype(np.float32)
+    R = orc.rows_stored(pol, ids, lq_ids, lqx, x, u, 1.2, k, orc.TAIL_REST)
+    for t in range(T):
+        if x[t] < 0:
+            assert R.out["valid"][t] == 0 and R.out["z_approx"][t] == 0.0
+            continue
+        z, usize = _z_stored_numpy(pol[t].astype(np.float64), ids[t], lq_ids[t].astype(np.float64), 1.2, k, 2)
+        assert R.out["z_approx"][t] == pytest.approx(z, rel=1e-12)
+        assert R.out["union_size"][t] == usize
+        o, kp = orc.row_stored(pol[t], ids[t], lq_ids[t], lqx[t], x[t], u[t], 1.2, k, 2)
+        assert o.z_approx == R.out["z_approx"][t] and o.mask == R.out["mask"][t]
+        np.testing.assert_array_equal(kp, R.topk_p[t])
