@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--grad", choices=["none", "bf16", "f32"], default="none",
                     help="also time jp_obrs_distill_grad (gradient of the distillation term w.r.t. the "
                          "actor logits, written in this dtype) and report it as \"distill_grad\"")
+    ap.add_argument("--stored", choices=["none", "drop", "kth", "rest"], default="none",
+                    help="also time jp_obrs_forward_stored (actor side as TopK_inf ids + log-probabilities, "
+                         "only the policy tensor is swept) with this rule and report it as \"stored_actor\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -180,6 +183,36 @@ def main():
                      "frac": g_bytes / (g_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "tokens_per_s": T / (g_avg * 1e-3)}
         del grad
 
+    stored_info = None
+    if args.stored != "none":
+        rule = {"drop": obrs.JP_TAIL_DROP, "kth": obrs.JP_TAIL_KTH, "rest": obrs.JP_TAIL_REST}[args.stored]
+        # the rollout phase's record of the actor, taken here from the two-tensor path's own outputs
+        fb = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, obrs.JP_FLAG_TOPK_LOGPROBS, dev)
+        obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, None, w.lam, w.k, w.c1, w.c2,
+                             obrs.JP_FLAG_TOPK_LOGPROBS, fb)
+        torch.cuda.synchronize()
+        s_ids, s_lq, s_lqx = fb.topk_actor, fb.topk_actor_logq, fb.logq
+        sb = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, 0, dev)
+        sev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps + 1)]
+        for a, b in sev:
+            a.record()
+            obrs.jp_obrs_forward_stored(w.policy, s_ids, s_lq, s_lqx, w.sampled_ids, w.uniforms, None, w.lam,
+                                        w.k, w.c1, w.c2, 0, rule, sb)
+            b.record()
+        torch.cuda.synchronize()
+        s_ms = sorted(a.elapsed_time(b) for a, b in sev[1:])
+        s_avg = sum(s_ms) / len(s_ms)
+        # one logit row, the stored list (ids + log-probs) and log q(x) in; per-token results and one id list out
+        s_bytes = T * (V * esz + w.k * 8 + 4 + 8 + 25 + w.k * 4)
+        sst = sb.stats()
+        stored_info = {"call": "jp_obrs_forward_stored (row stage + batch stage), rule " + args.stored,
+                       "ms_avg": s_avg, "ms_min": s_ms[0], "tokens_per_s": T / (s_avg * 1e-3),
+                       "algorithmic_bytes": s_bytes, "bound": "hbm", "achieved": s_bytes / (s_avg * 1e-3) / 1e9,
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": s_bytes / (s_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "kappa": sst.kappa, "mean_z_approx": sst.mean_z_approx}
+        del fb, sb
+
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)
         for _ in range(args.calibrate_copy):
@@ -230,6 +263,8 @@ def main():
     }
     if grad_info is not None:
         line["distill_grad"] = grad_info
+    if stored_info is not None:
+        line["stored_actor"] = stored_info
     print(json.dumps(line), flush=True)
 
 

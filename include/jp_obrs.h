@@ -171,6 +171,40 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * The whole hot path with the actor side in the form the rollout phase stores it (Alg. 1,
+ * Phase 1): per position the sampled token's log-probability log p_inf(a_t) and the k ids and
+ * log-probabilities of TopK_inf, instead of a [T, V] actor logit tensor.  Only the target model's
+ * logits are swept, so the bytes moved per token are halved.
+ *   a_t, mask_t: from actor_logprob_x[t] and log p(x_t)                  Eq. obrs_accept
+ *   V_k = TopK_inf U top-k(p)                                            Alg. 1 step 2
+ *   Z_approx,t = sum_{v in TopK_inf} min(q(v), p(v)/lambda)
+ *              + sum_{v in top-k(p), not in TopK_inf} min(qhat_t, p(v)/lambda)
+ * The paper does not say what q(v) is for a token of top-k(p) that TopK_inf does not hold; qhat_t
+ * is chosen by tail_rule:
+ *   JP_TAIL_DROP  such tokens contribute nothing (a lower bound of the two-tensor Z_approx)
+ *   JP_TAIL_KTH   the smallest stored probability (v is not among the k largest, so q(v) cannot
+ *                 exceed it: an upper bound of the two-tensor Z_approx)
+ *   JP_TAIL_REST  the mass the stored list leaves, 1 - sum of the stored probabilities, spread
+ *                 evenly over the other V - n tokens, capped by the JP_TAIL_KTH bound
+ * Batch stage (alpha_hat, kappa, w_t, rho_t) and every other convention as in jp_obrs_forward.
+ *   actor_topk_ids      device [T, k] int32; an id outside [0, V) marks an unused slot, of a
+ *                       repeated id the first occurrence counts; any order
+ *   actor_topk_logprob  device [T, k] fp32, log q of those ids
+ *   actor_logprob_x     device [T] fp32, log q(x_t)
+ * Outputs: logq is a copy of actor_logprob_x; topk_actor / topk_actor_logq are not written (they
+ * are inputs here).  JP_FLAG_EXACT_Z and JP_FLAG_DISTILL_KL need the actor row: JP_ERR_UNSUPPORTED.
+ * Workspace: jp_obrs_workspace_bytes.
+ */
+typedef enum jp_tail_rule { JP_TAIL_DROP = 0, JP_TAIL_KTH = 1, JP_TAIL_REST = 2 } jp_tail_rule;
+jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V, int64_t row_stride,
+                                 jp_dtype dt, const int32_t *actor_topk_ids,
+                                 const float *actor_topk_logprob, const float *actor_logprob_x,
+                                 const int32_t *sampled_ids, const float *uniforms,
+                                 const float *ref_logprob, const jp_obrs_params *prm,
+                                 jp_tail_rule tail_rule, const jp_obrs_outputs *out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gradient of the on-policy distillation term of Sec. 4.2 (3), Eq. distill_loss, with respect to
  * the actor logits.  The term per token is KL(SG(p_t) || q_t) with the target p_t held fixed and
  * q_t = softmax(actor logits), so d/d lq_t[v] = q_t(v) - p_t(v).  This call writes

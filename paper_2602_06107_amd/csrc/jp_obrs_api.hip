@@ -289,6 +289,55 @@ jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits, i
                          (hipStream_t)stream, uniforms != nullptr);
 }
 
+/* Whole hot path with the actor side as the rollout phase stored it (ids + log-probabilities). */
+jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V, int64_t row_stride,
+                                 jp_dtype dt, const int32_t *actor_topk_ids, const float *actor_topk_logprob,
+                                 const float *actor_logprob_x, const int32_t *sampled_ids,
+                                 const float *uniforms, const float *ref_logprob, const jp_obrs_params *prm,
+                                 jp_tail_rule tail_rule, const jp_obrs_outputs *out, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (!prm || !out) return JP_ERR_NULL;
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s != JP_OK) return s;
+    s = check_params(prm, V, true);
+    if (s != JP_OK) return s;
+    if (prm->flags & (JP_FLAG_EXACT_Z | JP_FLAG_DISTILL_KL)) return JP_ERR_UNSUPPORTED;   // need the actor row
+    if (tail_rule != JP_TAIL_DROP && tail_rule != JP_TAIL_KTH && tail_rule != JP_TAIL_REST) return JP_ERR_PARAM;
+    if (T > 0 && (!policy_logits || !sampled_ids || !actor_topk_ids || !actor_topk_logprob || !actor_logprob_x))
+        return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(policy_logits) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < jp_obrs_workspace_bytes(T, V, prm->k, dt, prm->flags)) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (T > 0) {
+        const Workspace w = carve(workspace, T);
+        jp::RowArgs a{};
+        a.actor = nullptr; a.policy = policy_logits; a.T = T; a.V = V; a.stride = row_stride;
+        a.ids = sampled_ids; a.uni = uniforms; a.lambda = prm->lambda; a.ln_lambda = log((double)prm->lambda);
+        a.k = prm->k;
+        a.accept = out->accept_prob ? out->accept_prob : w.accept;
+        a.logq = out->logq ? out->logq : w.logq;
+        a.logp = out->logp ? out->logp : w.logp;
+        a.logratio = out->logratio ? out->logratio : w.logratio;
+        a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+        a.kl = w.kl;
+        a.lse_q = w.lse_q; a.lse_p = w.lse_p;
+        a.mask = out->mask ? out->mask : w.mask;
+        a.rowflag = w.rowflag;
+        a.usize = out->union_size;
+        a.topk_a = nullptr; a.topk_p = out->topk_policy;
+        a.topk_a_lq = nullptr;
+        a.topk_p_lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) ? out->topk_policy_logp : nullptr;
+        a.stored_ids = actor_topk_ids; a.stored_logq = actor_topk_logprob; a.stored_logq_x = actor_logprob_x;
+        a.tail_rule = (int)tail_rule;
+        if (jp::launch_rows_stored(a, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
+    }
+    return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes, st,
+                         uniforms != nullptr);
+}
+
 /* Gradient of the distillation term with respect to the actor logits (second streaming pass). */
 jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
                                int64_t row_stride, jp_dtype dt, const float *row_scale, float scale,
@@ -332,6 +381,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 3; }
+int jp_obrs_abi_version(void) { return 4; }
 
 }  // extern "C"

@@ -34,6 +34,11 @@ struct RowArgs {
     int carry_in, carry_out;          // a row record is read before / written after this chunk
     unsigned char *state;             // [T] records of state_stride bytes (carry_state_bytes(k))
     int64_t state_stride;
+    // stored-actor form only: the actor side as ids + log-probabilities instead of a logit tensor
+    const int32_t *stored_ids;        // [T, k]
+    const float *stored_logq;         // [T, k]
+    const float *stored_logq_x;       // [T]
+    int tail_rule;
 };
 
 // Row record carried from one vocabulary chunk to the next, followed by the two top-k lists as
@@ -84,6 +89,7 @@ struct GradArgs {
 };
 
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
+hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st);   // a.actor unused
 hipError_t launch_distill_grad(const GradArgs &a, int dtype, int grad_dtype, hipStream_t st);
 // Two independent TN GEMMs sharing M, N and ldc (policy head and actor head of one vocabulary chunk).
 struct GemmArgs {

@@ -440,7 +440,7 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // the running row state (exponent reference and sum of both rows, sampled-token logits, the two
 // top-k lists so far with both logits of every entry) is read from / written to a per-row record,
 // and only the launch of the last chunk runs the union / normaliser / acceptance step.
-template <class ET, class KT, int KC, bool CARRY, bool DISTILL>
+template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false>
 __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
@@ -456,7 +456,9 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     constexpr int DS = 2 * KC / WAVE;                               // descriptor registers per lane
     constexpr int DESC_BYTES = 2 * C * (int)sizeof(Key);
     constexpr int CAND_BYTES = E * ((int)sizeof(SK) + 8);
-    constexpr int POOL_BYTES = ((DESC_BYTES > CAND_BYTES ? DESC_BYTES : CAND_BYTES) + 15) / 16 * 16;
+    constexpr int UNION_BYTES = (3 * KC + 2 * KC + (STORED ? 2 * KC : 0)) * 4;   // list 1, hash table, first-occurrence table
+    constexpr int POOL_BYTES0 = DESC_BYTES > CAND_BYTES ? DESC_BYTES : CAND_BYTES;
+    constexpr int POOL_BYTES = ((POOL_BYTES0 > UNION_BYTES ? POOL_BYTES0 : UNION_BYTES) + 15) / 16 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char pool[POOL_BYTES];
     Key *const s_desc0 = (Key *)pool;
     Key *const s_desc1 = s_desc0 + C;
@@ -466,7 +468,6 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     // The two ranked lists (ids, own logits, the other tensor's logits).  List 1 is only written
     // when the candidates of tensor 1 are no longer needed and takes their place in the pool.
     __shared__ uint32_t list0[3 * KC];
-    static_assert(POOL_BYTES >= (3 * KC + 2 * KC) * 4, "list 1 and the union hash table share the pool");
     uint32_t *const l_id[2] = {list0, (uint32_t *)pool};
     float *const l_a[2] = {(float *)(list0 + KC), (float *)pool + KC};
     float *const l_b[2] = {(float *)(list0 + 2 * KC), (float *)pool + 2 * KC};
@@ -543,10 +544,10 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     }
 
     auto consume = [&](const float (&fq)[VEC], const float (&fp)[VEC], uint32_t c, bool valid) {
-        const float mq = max_of<VEC>(fq), mp = max_of<VEC>(fp);
-        const bool pq = valid && (mq >= sq.tauv);
+        const float mq = STORED ? 0.f : max_of<VEC>(fq), mp = max_of<VEC>(fp);
+        const bool pq = !STORED && valid && (mq >= sq.tauv);
         const bool pp = valid && (mp >= sp.tauv);
-        const uint64_t bq = __ballot(pq), bp = __ballot(pp);
+        const uint64_t bq = STORED ? 0 : __ballot(pq), bp = __ballot(pp);
         if (bq | bp) {
             if (bq) offer_chunk<KT, C, NS>(sq, s_desc0, mq, c, pq, k);
             if (bp) offer_chunk<KT, C, NS>(sp, s_desc1, mp, c, pp, k);
@@ -557,7 +558,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
                 if (__ballot(rp)) raise_reference(sp, mp, pp);
             }
         }
-        sq.s += sum_exp2<VEC>(fq, sq.M2);
+        if constexpr (!STORED) sq.s += sum_exp2<VEC>(fq, sq.M2);
         if constexpr (DISTILL) sp.s += sum_exp2_kl<VEC>(fp, fq, sp.M2, sp.d);
         else sp.s += sum_exp2<VEC>(fp, sp.M2);
     };
@@ -594,7 +595,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
             float fq[VEC], fp[VEC];
             const bool valid = c < nchunks;
             if (valid) {
-                load_chunk<ET>(rowq, c, nfull, tail, fq);
+                if constexpr (!STORED) load_chunk<ET>(rowq, c, nfull, tail, fq);
                 load_chunk<ET>(rowp, c, nfull, tail, fp);
             } else {
 #pragma unroll
@@ -607,13 +608,14 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
     const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
     const double Dp = DISTILL ? wave_sum((double)sp.d) : 0.0;
-    const double lse_q = ((double)sq.M2 + log2_of_sum(Sq)) * LN2_D;
+    // stored form: the actor side arrives as log-probabilities, i.e. logits whose log-sum-exp is 0
+    const double lse_q = STORED ? 0.0 : ((double)sq.M2 + log2_of_sum(Sq)) * LN2_D;
     const double lse_p = ((double)sp.M2 + log2_of_sum(Sp)) * LN2_D;
     const double ln_lambda = A.ln_lambda;
 
     // logits of the sampled token (from this chunk if it holds x, else the carried ones)
     const bool x_here = (int64_t)x >= id_base && (int64_t)x < id_base + V;
-    const float xq = x_here ? ET::load1(rowq, (int64_t)x - id_base) : xq_in;
+    const float xq = STORED ? A.stored_logq_x[t] : (x_here ? ET::load1(rowq, (int64_t)x - id_base) : xq_in);
     const float xp = x_here ? ET::load1(rowp, (int64_t)x - id_base) : xp_in;
     const double lq_x = (double)xq, lp_x = (double)xp;
     const double logq_x = lq_x - lse_q, logp_x = lp_x - lse_p;
@@ -629,13 +631,13 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     // The value bits of the k-th largest chunk maximum are enough: every chunk at or above that
     // value is expanded and the element ranking below is exact.  Only a large plateau of equal
     // maxima makes the select run to the last bit (leaving exactly k chunks).
-    nc[0] = uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, 2 * KC, kth[0]));
+    nc[0] = STORED ? 0 : uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, 2 * KC, kth[0]));
     nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc1, sp.cnt, k, false, 2 * KC, kth[1]));
     Key dk[2][DS];                                                  // at most 2*KC survive per tensor
 #pragma unroll
     for (int sl = 0; sl < DS; ++sl) {
         const int e = sl * WAVE + lane;
-        dk[0][sl] = e < nc[0] ? s_desc0[e] : (Key)0;
+        dk[0][sl] = (!STORED && e < nc[0]) ? s_desc0[e] : (Key)0;
         dk[1][sl] = e < nc[1] ? s_desc1[e] : (Key)0;
     }
     lds_sync();                                                     // the pool now belongs to the candidates
@@ -673,7 +675,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
         auto fill_other = [&]() {
             lds_sync();
             for (int e = filled + lane; e < nS; e += WAVE)
-                s_oth[e] = __float_as_uint(ET::load1(rowB, (int64_t)s_cid[e] - id_base));
+                s_oth[e] = STORED ? 0u : __float_as_uint(ET::load1(rowB, (int64_t)s_cid[e] - id_base));
             filled = nS;
         };
         // Sort the nS buffered candidates.  Candidates are buffered in ascending id order among
@@ -808,7 +810,8 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
         }
         lds_sync();
     };
-    expand(std::integral_constant<int, 0>{});
+    if constexpr (STORED) nl[0] = 0;
+    else expand(std::integral_constant<int, 0>{});
     expand(std::integral_constant<int, 1>{});
 
     if (carry_out) {                      // hand the row state to the launch of the next chunk
@@ -835,29 +838,89 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
     // In the log domain min(q, p/lambda) = exp(min(lq - LSEq, lp - LSEp - ln lambda)).
     double zsum = 0.0;
     int ucount = 0;
-    for (int r = lane; r < nl[0]; r += WAVE) {
-        const double dq = (double)l_a[0][r] - lse_q;
-        const double dp = (double)l_b[0][r] - lse_p - ln_lambda;
-        zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
-        ucount += 1;
-        if (A.topk_a) A.topk_a[t * k + r] = (int32_t)l_id[0][r];
-        if (A.topk_a_lq) A.topk_a_lq[t * k + r] = finite_row ? (float)dq : NaN;
-    }
     // Membership of the policy list's ids in the actor list through a small open-addressing hash
     // table (load factor <= 1/2) in the LDS pool, behind list 1.
     constexpr int HT = 2 * KC;
     uint32_t *const tab = (uint32_t *)pool + 3 * KC;
-    lds_sync();
-    for (int e = lane; e < HT; e += WAVE) tab[e] = 0xffffffffu;
-    lds_sync();
-    for (int r = lane; r < nl[0]; r += WAVE) {
-        const uint32_t id = l_id[0][r];
+    auto table_insert = [&](uint32_t id) {                  // returns the slot that holds id
         uint32_t slot = (id * 2654435761u) >> 7 & (HT - 1);
         for (int tries = 0; tries < HT; ++tries) {
             const uint32_t old = atomicCAS(&tab[slot], 0xffffffffu, id);
             if (old == 0xffffffffu || old == id) break;
             slot = (slot + 1) & (HT - 1);
         }
+        return slot;
+    };
+    double tail_dq = 0.0;                 // stored form: log q assumed for a token outside the stored list
+    if constexpr (STORED) {
+        // The actor list as the rollout phase stored it (Alg. 1, Phase 1): ids and log-probabilities.
+        // A slot with an id outside [0, V) is unused; of a repeated id the first occurrence counts
+        // (decided by an atomic minimum over positions, so the outcome does not depend on timing).
+        uint32_t *const first = tab + HT;
+        constexpr int SR = KC / WAVE;
+        uint32_t sid[SR], sslot[SR];
+        float slq[SR];
+        lds_sync();
+        for (int e = lane; e < 2 * HT; e += WAVE) tab[e] = 0xffffffffu;     // table and first[]
+        lds_sync();
+#pragma unroll
+        for (int s2 = 0; s2 < SR; ++s2) {
+            const int r = s2 * WAVE + lane;
+            const int32_t raw_id = r < k ? A.stored_ids[t * k + r] : -1;
+            const bool ok = raw_id >= 0 && (int64_t)raw_id < V;
+            sid[s2] = ok ? (uint32_t)raw_id : 0xffffffffu;
+            slq[s2] = ok ? A.stored_logq[t * k + r] : 0.f;
+            sslot[s2] = 0;
+            if (ok) {
+                sslot[s2] = table_insert(sid[s2]);
+                atomicMin(&first[sslot[s2]], (uint32_t)r);
+            }
+        }
+        lds_sync();
+        float kth = __uint_as_float(0x7f800000u);           // smallest stored log-probability
+        double mass = 0.0;
+        int n = 0;
+#pragma unroll
+        for (int s2 = 0; s2 < SR; ++s2) {
+            const int r = s2 * WAVE + lane;
+            const bool keep = sid[s2] != 0xffffffffu && first[sslot[s2]] == (uint32_t)r;
+            if (keep) {
+                const double dq = (double)slq[s2];
+                const double dp = (double)ET::load1(rowp, (int64_t)sid[s2]) - lse_p - ln_lambda;
+                zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
+                mass += (double)__builtin_amdgcn_exp2f((float)(dq * LOG2E_D));
+                kth = fminf(kth, slq[s2]);
+                ucount += 1;
+            }
+        }
+        n = wave_sum_i(ucount);
+        kth = -uniform_f(wave_max(-kth));
+        mass = wave_sum(mass);
+        if (n == 0) kth = 0.f;                              // nothing stored: the bound is log 1
+        const double neg_inf_d = -__builtin_inf();
+        if (A.tail_rule == 0 || (int64_t)n == V) {
+            tail_dq = neg_inf_d;
+        } else if (A.tail_rule == 1) {
+            tail_dq = (double)kth;
+        } else {
+            const double rest = mass < 1.0 ? 1.0 - mass : 0.0;
+            const double share = rest / (double)(V - n);
+            tail_dq = share > 0.0 ? (double)(__builtin_amdgcn_logf((float)share)) * LN2_D : neg_inf_d;
+            tail_dq = tail_dq < (double)kth ? tail_dq : (double)kth;
+        }
+    } else {
+        for (int r = lane; r < nl[0]; r += WAVE) {
+            const double dq = (double)l_a[0][r] - lse_q;
+            const double dp = (double)l_b[0][r] - lse_p - ln_lambda;
+            zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
+            ucount += 1;
+            if (A.topk_a) A.topk_a[t * k + r] = (int32_t)l_id[0][r];
+            if (A.topk_a_lq) A.topk_a_lq[t * k + r] = finite_row ? (float)dq : NaN;
+        }
+        lds_sync();
+        for (int e = lane; e < HT; e += WAVE) tab[e] = 0xffffffffu;
+        lds_sync();
+        for (int r = lane; r < nl[0]; r += WAVE) table_insert(l_id[0][r]);
     }
     lds_sync();
     for (int r = lane; r < nl[1]; r += WAVE) {
@@ -871,7 +934,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ?
             slot = (slot + 1) & (HT - 1);
         }
         const double dp0 = (double)l_a[1][r] - lse_p;
-        const double dq = (double)l_b[1][r] - lse_q;
+        const double dq = STORED ? tail_dq : (double)l_b[1][r] - lse_q;
         const double dp = dp0 - ln_lambda;
         if (!dup) {
             zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
@@ -1208,6 +1271,27 @@ hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st)
         return launch_rows_k<Bf16Elem, Key64>(a, st);
     }
     return launch_rows_k<F32Elem, Key64>(a, st);
+}
+
+template <class ET, class KT>
+static hipError_t launch_rows_stored_k(const RowArgs &a, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, true>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false, true>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    if (dtype == JP_BF16) {
+        const int64_t nchunks = (a.V + Bf16Elem::VEC - 1) / Bf16Elem::VEC;
+        if (nchunks <= 65535) return launch_rows_stored_k<Bf16Elem, Key32>(a, st);
+        return launch_rows_stored_k<Bf16Elem, Key64>(a, st);
+    }
+    return launch_rows_stored_k<F32Elem, Key64>(a, st);
 }
 
 hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)

@@ -20,11 +20,13 @@ JP_K_MAX = 256
 JP_F32, JP_BF16 = 0, 1
 JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED, JP_FLAG_DISTILL_KL = 1, 2, 4, 8
 JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
+JP_TAIL_DROP, JP_TAIL_KTH, JP_TAIL_REST = 0, 1, 2
 (JP_OK, JP_ERR_NULL, JP_ERR_SHAPE, JP_ERR_PARAM, JP_ERR_ALIGN, JP_ERR_WORKSPACE,
  JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
 
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
            "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
+           "jp_obrs_forward_stored",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -79,6 +81,11 @@ _lib.jp_obrs_distill_grad.restype = C.c_int
 _lib.jp_obrs_distill_grad.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                                       C.c_void_p, C.c_float, C.c_void_p, C.c_int64, C.c_int,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_forward_stored.restype = C.c_int
+_lib.jp_obrs_forward_stored.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(Params), C.c_int, C.POINTER(Outputs), C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -192,6 +199,28 @@ def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c
     st = _lib.jp_obrs_forward(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
                               _p(ref_logprob), C.byref(prm), C.byref(buf.out), _p(buf.workspace),
                               buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_forward_stored(policy, actor_topk_ids, actor_topk_logprob, actor_logprob_x, sampled_ids,
+                           uniforms, ref_logprob, lam, k, c1, c2, flags, tail_rule, buf: Buffers,
+                           stream=None) -> None:
+    """Whole hot path with the actor side as stored by the rollout phase (ids + log-probabilities)."""
+    if policy.dim() != 2 or policy.stride(1) != 1:
+        raise ValueError("policy logits must be a [T, V] tensor with contiguous rows")
+    T, V = policy.shape
+    stride = policy.stride(0) if T > 1 else max(policy.stride(0), V)
+    for t_, shape, dtype in ((actor_topk_ids, (T, k), torch.int32), (actor_topk_logprob, (T, k), torch.float32),
+                             (actor_logprob_x, (T,), torch.float32)):
+        if tuple(t_.shape) != shape or t_.dtype != dtype or not t_.is_contiguous():
+            raise ValueError("stored actor side: contiguous int32 [T, k], float32 [T, k], float32 [T]")
+    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    st = _lib.jp_obrs_forward_stored(_p(policy), T, V, stride, _dtype_code(policy), _p(actor_topk_ids),
+                                     _p(actor_topk_logprob), _p(actor_logprob_x), _p(sampled_ids),
+                                     _p(uniforms), _p(ref_logprob), C.byref(prm), int(tail_rule),
+                                     C.byref(buf.out), _p(buf.workspace), buf.workspace.numel(),
+                                     _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 

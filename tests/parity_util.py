@@ -40,8 +40,9 @@ def _close(got, want, rel, what, abs_tol=0.0):
                            f"want {want.flat[np.argmax(err - bound)]!r}")
 
 
-def check_rows(buf, w, R, rows=None, flags=0, tol=None):
-    """Per-row outputs of the HIP path against oracle rows R (for all rows or the sampled ones)."""
+def check_rows(buf, w, R, rows=None, flags=0, tol=None, stored=False):
+    """Per-row outputs of the HIP path against oracle rows R (for all rows or the sampled ones).
+    stored=True: the stored-actor form, where the actor list is an input and is not written."""
     tol = TOL[w.actor.dtype] if tol is None else tol
     idx = np.arange(w.T) if rows is None else np.asarray(rows)
     o = R.out
@@ -53,10 +54,12 @@ def check_rows(buf, w, R, rows=None, flags=0, tol=None):
         for n in ("accept_prob", "logq", "logp", "logratio", "z_approx"):
             assert np.all(g[n][~valid] == 0.0), n
         assert np.all(g["mask"][~valid] == 0)
-        assert np.all(g["topk_actor"][~valid] == -1) and np.all(g["topk_policy"][~valid] == -1)
+        assert np.all(g["topk_policy"][~valid] == -1)
+        assert stored or np.all(g["topk_actor"][~valid] == -1)
 
     v = valid
-    np.testing.assert_array_equal(g["topk_actor"][v], R.topk_q[v], err_msg="top-k(q) ids")
+    if not stored:
+        np.testing.assert_array_equal(g["topk_actor"][v], R.topk_q[v], err_msg="top-k(q) ids")
     np.testing.assert_array_equal(g["topk_policy"][v], R.topk_p[v], err_msg="top-k(p) ids")
     np.testing.assert_array_equal(g["union_size"][v], o["union_size"][v], err_msg="|V_k|")
     _close(g["logq"][v], o["logq_x"][v], 0.0, "log q(x)", abs_tol=tol)
@@ -69,14 +72,15 @@ def check_rows(buf, w, R, rows=None, flags=0, tol=None):
     if flags & obrs.JP_FLAG_DISTILL_KL:
         _close(g["distill_kl"][v], o["kl_p_q"][v], tol, "KL(p||q)", abs_tol=tol)
     if flags & obrs.JP_FLAG_TOPK_LOGPROBS:
-        a64 = wl.logits_to_float64(w.actor[torch.as_tensor(idx, device=w.actor.device)])
         p64 = wl.logits_to_float64(w.policy[torch.as_tensor(idx, device=w.actor.device)])
-        tq = np.where(valid[:, None], R.topk_q, 0).astype(np.int64)
         tp = np.where(valid[:, None], R.topk_p, 0).astype(np.int64)
-        want_q = np.take_along_axis(a64, tq, 1) - o["lse_q"][:, None]
         want_p = np.take_along_axis(p64, tp, 1) - o["lse_p"][:, None]
-        _close(g["topk_actor_logq"][v], want_q[v], 0.0, "top-k log q", abs_tol=tol)
         _close(g["topk_policy_logp"][v], want_p[v], 0.0, "top-k log p", abs_tol=tol)
+        if not stored:
+            a64 = wl.logits_to_float64(w.actor[torch.as_tensor(idx, device=w.actor.device)])
+            tq = np.where(valid[:, None], R.topk_q, 0).astype(np.int64)
+            want_q = np.take_along_axis(a64, tq, 1) - o["lse_q"][:, None]
+            _close(g["topk_actor_logq"][v], want_q[v], 0.0, "top-k log q", abs_tol=tol)
 
     # Bernoulli mask: exact away from the threshold, either value inside the band
     u = w.uniforms.cpu().numpy()[idx].astype(np.float64)
