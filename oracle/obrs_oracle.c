@@ -421,9 +421,22 @@ void jpo_distill_grad(const void *actor, const void *policy, int dtype, int64_t 
  * Z_t = kappa Z_approx;  w = Z_t max(lambda, p(x)/q(x));
  * rho = min(w, c1) * min(p_ref(x)/p(x), c2)   (second factor 1 if no ref).
  * use_expected_alpha != 0 replaces alpha_hat by the mean of a(x).        */
-void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double lambda,
-               double c1, double c2, const double *ref_logprob, int use_expected_alpha,
-               jpo_batch_out *b, double *w_out, double *rho_out)
+/* The adjustment function F of the importance weight (Sec. 2, related work; Eq. obrs_ppo applies it
+ * to p_target / p'_inf):  0 = truncation F(w) = min(w, c1) (TIS; the paper's choice, Alg. 1 step 3),
+ * 1 = identity F(w) = w,  2 = two-sided truncation F(w) = w if lo <= w <= hi, else 0.             */
+enum { JPO_F_TRUNCATE = 0, JPO_F_IDENTITY = 1, JPO_F_BAND = 2 };
+
+double jpo_adjust(double w, int f_mode, double c1, double lo, double hi)
+{
+    if (f_mode == JPO_F_IDENTITY) return w;
+    if (f_mode == JPO_F_BAND) return (w >= lo && w <= hi) ? w : 0.0;
+    return w < c1 ? w : c1;
+}
+
+void jpo_batch_f(const jpo_row_out *rows, const int32_t *mask, int64_t T, double lambda,
+                 int f_mode, double c1, double f_lo, double f_hi, double c2,
+                 const double *ref_logprob, int use_expected_alpha,
+                 jpo_batch_out *b, double *w_out, double *rho_out)
 {
     memset(b, 0, sizeof *b);
     double sz = 0.0, sze = 0.0, sa = 0.0, skl = 0.0;
@@ -454,7 +467,7 @@ void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double l
         double z_t = b->kappa * rows[t].z_approx;
         double ratio = exp(rows[t].logratio);
         double w = z_t * (lambda > ratio ? lambda : ratio);
-        double rho = w < c1 ? w : c1;
+        double rho = jpo_adjust(w, f_mode, c1, f_lo, f_hi);
         if (ref_logprob) {
             double rr = exp(ref_logprob[t] - rows[t].logp_x);
             rho *= rr < c2 ? rr : c2;
@@ -462,6 +475,31 @@ void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double l
         if (w_out) w_out[t] = w;
         if (rho_out) rho_out[t] = rho;
     }
+}
+
+void jpo_batch(const jpo_row_out *rows, const int32_t *mask, int64_t T, double lambda,
+               double c1, double c2, const double *ref_logprob, int use_expected_alpha,
+               jpo_batch_out *b, double *w_out, double *rho_out)
+{
+    jpo_batch_f(rows, mask, T, lambda, JPO_F_TRUNCATE, c1, 0.0, 0.0, c2, ref_logprob,
+                use_expected_alpha, b, w_out, rho_out);
+}
+
+/* ---- log-probability of one token per row under one logit tensor ---------------------------
+ * log softmax(l_t)[x_t] = l_t[x_t] - LSE(l_t): how log p_ref(a_t) (Alg. 1, Phase 2 step 1) is read
+ * off a third logit tensor.  Padding rows (x < 0) give 0, ids outside the vocabulary NaN.      */
+void jpo_token_logprob(const void *logits, int dtype, int64_t T, int64_t V, int64_t row_stride,
+                       const int32_t *x, double *out)
+{
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    double *l = (double *)malloc((size_t)V * sizeof(double));
+    for (int64_t t = 0; t < T; ++t) {
+        if (x[t] < 0) { out[t] = 0.0; continue; }
+        if (x[t] >= V) { out[t] = NAN; continue; }
+        jpo_widen_row((const char *)logits + (size_t)t * (size_t)row_stride * esz, dtype, V, l);
+        out[t] = l[x[t]] - jpo_logsumexp(l, V);
+    }
+    free(l);
 }
 
 int jpo_max_threads(void)

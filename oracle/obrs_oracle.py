@@ -98,6 +98,15 @@ def lib():
         l.jpo_rows_stored.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
                                       C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int]
+        l.jpo_adjust.restype = C.c_double
+        l.jpo_adjust.argtypes = [C.c_double, C.c_int, C.c_double, C.c_double, C.c_double]
+        l.jpo_batch_f.restype = None
+        l.jpo_batch_f.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double, C.c_int, C.c_double,
+                                  C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_int,
+                                  C.POINTER(BatchOut), C.c_void_p, C.c_void_p]
+        l.jpo_token_logprob.restype = None
+        l.jpo_token_logprob.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
+                                        C.c_void_p]
         l.jpo_max_threads.restype = C.c_int
         l.jpo_widen_row.restype = None
         l.jpo_widen_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
@@ -195,6 +204,41 @@ def batch(rows_out: np.ndarray, mask, lam: float, c1: float, c2: float, ref_logp
     lib().jpo_batch(_ptr(rows_out), _ptr(mask), T, float(lam), float(c1), float(c2), _ptr(ref),
                     int(use_expected_alpha), C.byref(b), _ptr(w), _ptr(rho))
     return b, w, rho
+
+
+F_TRUNCATE, F_IDENTITY, F_BAND = 0, 1, 2
+
+
+def adjust(w: float, f_mode: int, c1: float, lo: float = 0.0, hi: float = 0.0) -> float:
+    """F(w): truncation min(w, c1), identity, or two-sided truncation (Sec. 2)."""
+    return lib().jpo_adjust(float(w), int(f_mode), float(c1), float(lo), float(hi))
+
+
+def batch_f(rows_out: np.ndarray, mask, lam: float, f_mode: int, c1: float, f_lo: float, f_hi: float,
+            c2: float, ref_logprob=None, use_expected_alpha: bool = False):
+    """``batch`` with a selectable adjustment function F -> (BatchOut, w[T], rho[T])."""
+    rows_out = np.ascontiguousarray(rows_out, dtype=ROW_DTYPE)
+    T = rows_out.size
+    mask = np.ascontiguousarray(mask, dtype=np.int32)
+    ref = None if ref_logprob is None else _f64(ref_logprob)
+    b = BatchOut()
+    w = np.empty(T, dtype=np.float64)
+    rho = np.empty(T, dtype=np.float64)
+    lib().jpo_batch_f(_ptr(rows_out), _ptr(mask), T, float(lam), int(f_mode), float(c1), float(f_lo),
+                      float(f_hi), float(c2), _ptr(ref), int(use_expected_alpha), C.byref(b), _ptr(w),
+                      _ptr(rho))
+    return b, w, rho
+
+
+def token_logprob(logits: np.ndarray, x) -> np.ndarray:
+    """log softmax(logits[t])[x[t]] per row (float32 / float64 / bf16 bits storage) -> float64 [T]."""
+    assert logits.ndim == 2 and logits.strides[1] == logits.itemsize
+    a, code = storage_view(logits)
+    T, V = a.shape
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    out = np.empty(T, dtype=np.float64)
+    lib().jpo_token_logprob(_ptr(a), code, T, V, a.strides[0] // a.itemsize, _ptr(x), _ptr(out))
+    return out
 
 
 def distill_grad_row(lq, lp, weight: float = 1.0) -> np.ndarray:

@@ -51,6 +51,12 @@ MUTANTS = [
      "double rest = 1.0 - mass;", "double rest = 1.0;"),
     ("stored form: tokens of TopK_new outside the stored list are dropped under every rule",
      "z += kept_mass(tail, lp[v] - lse_p, lambda);\n            ++usize;", "++usize;"),
+    ("band adjustment keeps the weights outside the band",
+     "return (w >= lo && w <= hi) ? w : 0.0;", "return (w >= lo && w <= hi) ? 0.0 : w;"),
+    ("identity adjustment still truncates",
+     "if (f_mode == JPO_F_IDENTITY) return w;", "if (f_mode == JPO_F_IDENTITY) return w < c1 ? w : c1;"),
+    ("token log-probability forgets the log-sum-exp",
+     "out[t] = l[x[t]] - jpo_logsumexp(l, V);", "out[t] = l[x[t]];"),
     ("distillation gradient has the wrong sign",
      "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
     ("distillation gradient drops the row weight",

@@ -589,3 +589,53 @@ def test_stored_actor_form_unused_slots_duplicates_and_batch_driver():
         o, kp = orc.row_stored(pol[t], ids[t], lq_ids[t], lqx[t], x[t], u[t], 1.2, k, 2)
         assert o.z_approx == R.out["z_approx"][t] and o.mask == R.out["mask"][t]
         np.testing.assert_array_equal(kp, R.topk_p[t])
+
+
+# ---- adjustment functions F (Sec. 2) and the third distribution's token log-probability -----------
+
+def test_adjustment_functions_closed_forms():
+    assert orc.adjust(0.7, orc.F_TRUNCATE, 3.0) == 0.7 and orc.adjust(5.0, orc.F_TRUNCATE, 3.0) == 3.0
+    assert orc.adjust(5.0, orc.F_IDENTITY, 3.0) == 5.0
+    for w, want in ((0.4, 0.0), (0.5, 0.5), (1.3, 1.3), (2.0, 2.0), (2.01, 0.0)):
+        assert orc.adjust(w, orc.F_BAND, 3.0, 0.5, 2.0) == want
+    # in the batch stage: w = kappa Z max(lambda, p/q); rho = F(w) min(p_ref/p, c2)
+    rows = np.zeros(3, dtype=orc.ROW_DTYPE)
+    rows["valid"] = 1
+    rows["z_approx"] = [0.5, 0.25, 0.75]
+    rows["accept"] = [1.0, 0.5, 0.25]
+    rows["logratio"] = np.log([4.0, 0.5, 1.0])
+    rows["logp_x"] = np.log([0.2, 0.1, 0.3])
+    mask = [1, 1, 0]
+    ref = np.log([0.1, 0.4, 0.3])
+    kappa = (2 / 3) / 0.5
+    w_want = kappa * np.array([0.5 * 4.0, 0.25 * 1.0, 0.75 * 1.0])       # lambda = 1
+    second = np.minimum(np.array([0.5, 4.0, 1.0]), 3.0)
+    for mode, F in ((orc.F_TRUNCATE, lambda w: np.minimum(w, 1.5)), (orc.F_IDENTITY, lambda w: w),
+                    (orc.F_BAND, lambda w: np.where((w >= 0.5) & (w <= 2.0), w, 0.0))):
+        b, w, rho = orc.batch_f(rows, mask, 1.0, mode, 1.5, 0.5, 2.0, 3.0, ref)
+        assert b.kappa == pytest.approx(kappa, rel=1e-14)
+        np.testing.assert_allclose(w, w_want, rtol=1e-14)
+        np.testing.assert_allclose(rho, F(w_want) * second, rtol=1e-14)
+    b0, w0, rho0 = orc.batch(rows, mask, 1.0, 1.5, 3.0, ref)             # the default is the truncation
+    b1, w1, rho1 = orc.batch_f(rows, mask, 1.0, orc.F_TRUNCATE, 1.5, 9.0, 9.0, 3.0, ref)
+    np.testing.assert_array_equal(rho0, rho1)
+
+
+def test_token_logprob_against_scipy_log_softmax():
+    rng = np.random.default_rng(444)
+    T, V = 7, 123
+    l32 = rng.normal(0, 3, (T, V)).astype(np.float32)
+    x = np.array([0, 5, -1, 122, V, 60, 7], dtype=np.int32)
+    got = orc.token_logprob(l32, x)
+    ls = scipy.special.log_softmax(l32.astype(np.float64), axis=1)
+    for t in range(T):
+        if x[t] < 0:
+            assert got[t] == 0.0
+        elif x[t] >= V:
+            assert math.isnan(got[t])
+        else:
+            assert got[t] == pytest.approx(ls[t, x[t]], abs=1e-13)
+    bits = (l32.view(np.uint32) >> 16).astype(np.uint16)
+    wide = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    gb = orc.token_logprob(bits, np.full(T, 3, np.int32))
+    np.testing.assert_allclose(gb, scipy.special.log_softmax(wide, axis=1)[:, 3], atol=1e-13)
