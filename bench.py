@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--stored", choices=["none", "drop", "kth", "rest"], default="none",
                     help="also time jp_obrs_forward_stored (actor side as TopK_inf ids + log-probabilities, "
                          "only the policy tensor is swept) with this rule and report it as \"stored_actor\"")
+    ap.add_argument("--token-logprob", action="store_true",
+                    help="also time jp_obrs_token_logprob (log-probability of the sampled token under one "
+                         "more logit tensor, one sweep) and report it as \"token_logprob\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -213,6 +216,23 @@ def main():
                        "kappa": sst.kappa, "mean_z_approx": sst.mean_z_approx}
         del fb, sb
 
+    logprob_info = None
+    if args.token_logprob:
+        lp_out = torch.empty(T, dtype=torch.float32, device=dev)
+        lev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps + 1)]
+        for a, b in lev:
+            a.record()
+            obrs.jp_obrs_token_logprob(w.policy, w.sampled_ids, lp_out)
+            b.record()
+        torch.cuda.synchronize()
+        l_ms = sorted(a.elapsed_time(b) for a, b in lev[1:])
+        l_avg = sum(l_ms) / len(l_ms)
+        l_bytes = T * (V * esz + 4 + 4)
+        logprob_info = {"kernel": "token_logprob_kernel<bf16>", "kernel_ms_avg": l_avg, "kernel_ms_min": l_ms[0],
+                        "algorithmic_bytes": l_bytes, "bound": "hbm", "achieved": l_bytes / (l_avg * 1e-3) / 1e9,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": l_bytes / (l_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)
         for _ in range(args.calibrate_copy):
@@ -265,6 +285,8 @@ def main():
         line["distill_grad"] = grad_info
     if stored_info is not None:
         line["stored_actor"] = stored_info
+    if logprob_info is not None:
+        line["token_logprob"] = logprob_info
     print(json.dumps(line), flush=True)
 
 

@@ -11,7 +11,7 @@
  *   Z_t (diagnostic) = sum_{v in V} min(q(v), p(v)/lambda)            Sec. 4.1, Eq. obrs_dist
  *   alpha_hat  = accepted / proposed,  kappa = alpha_hat / mean_t Z_approx,t      Sec. 4.4.2
  *   w_t        = kappa Z_approx,t max(lambda, p(x_t)/q(x_t))          Alg. 1 step 3
- *   rho_t      = min(w_t, c1) min(p_ref(x_t)/p(x_t), c2)              Alg. 1 step 3
+ *   rho_t      = F(w_t) min(p_ref(x_t)/p(x_t), c2), F(w) = min(w, c1)  Alg. 1 step 3; Sec. 2 for other F
  *   KL_t (optional) = sum_v p(v) (log p(v) - log q(v))                Sec. 4.2 (3), Eq. distill_loss
  *
  * Conventions
@@ -70,12 +70,19 @@ enum {                          /* bits of jp_obrs_stats.error_flags */
     JP_DATA_ERR_EMPTY = 4       /* no valid row: kappa is NaN                */
 };
 
+/* Adjustment function F applied to w_t = p_target(x_t)/p'_inf(x_t) in rho_t (Eq. obrs_ppo; the
+ * choices are those of Sec. 2): the truncation min(w, c1) that Alg. 1 step 3 uses (TIS), the
+ * identity, or the two-sided truncation that keeps w inside [f_lo, f_hi] and zeroes it outside. */
+typedef enum jp_adjust { JP_F_TRUNCATE = 0, JP_F_IDENTITY = 1, JP_F_BAND = 2 } jp_adjust;
+
 typedef struct jp_obrs_params {
     float lambda;               /* rejection threshold, > 0 (paper default 1.0)            */
     int32_t k;                  /* top-k count per distribution, 1 <= k <= min(V, JP_K_MAX) */
     float c1;                   /* clip of w_OBRS, > 0 (+inf disables)                     */
     float c2;                   /* clip of p_ref/p, > 0 (+inf disables)                    */
     uint32_t flags;             /* JP_FLAG_*                                               */
+    uint32_t f_mode;            /* jp_adjust; 0 = the paper's truncation                   */
+    float f_lo, f_hi;           /* JP_F_BAND only: 0 <= f_lo <= f_hi                       */
 } jp_obrs_params;
 
 /* Batch statistics, written to device memory by the finalize stage (Sec. 4.4.2). */
@@ -203,6 +210,35 @@ jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V
                                  const float *ref_logprob, const jp_obrs_params *prm,
                                  jp_tail_rule tail_rule, const jp_obrs_outputs *out,
                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * log-probability of the sampled token under one more logit tensor,
+ *   out[t] = logits[t, x_t] - log sum_v exp(logits[t, v]),
+ * e.g. log p_ref(a_t) of Alg. 1 (Phase 2, step 1) when p_ref and p_new are separate tensors: its
+ * result is the ref_logprob argument of jp_obrs_forward.  One sweep of the tensor.  Padding rows
+ * (x_t < 0) give 0; an id >= V or a non-finite log-sum-exp gives NaN.  No workspace.
+ */
+jp_status jp_obrs_token_logprob(const void *logits, int64_t T, int64_t V, int64_t row_stride,
+                                jp_dtype dt, const int32_t *sampled_ids, float *out_logprob,
+                                void *stream);
+
+/*
+ * The three-distribution form of Eq. obrs_ppo / Alg. 1: rollout logits (p_inf), the updated
+ * policy's logits (p_new) and the reference policy's logits (p_ref) as separate tensors, with the
+ * OBRS target chosen by `target_is_ref` (Sec. 4.3: either may serve as p_target).
+ *   target_is_ref == 0: p_target = p_new; the factor p_ref(x)/p_target(x) of rho_t is computed from
+ *                       a sweep of policy_ref (jp_obrs_token_logprob into the workspace)
+ *   target_is_ref != 0: p_target = p_ref; that factor is 1 and policy_new is not read (may be NULL)
+ * Everything else as jp_obrs_forward on (actor, p_target).  Workspace:
+ * jp_obrs_workspace_bytes(...) + 4 T rounded up to 256 bytes (jp_obrs_forward3_workspace_bytes).
+ */
+size_t jp_obrs_forward3_workspace_bytes(int64_t T, int64_t V, int32_t k, jp_dtype dt, uint32_t flags);
+jp_status jp_obrs_forward3(const void *actor_logits, const void *policy_new_logits,
+                           const void *policy_ref_logits, int32_t target_is_ref,
+                           int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                           const int32_t *sampled_ids, const float *uniforms,
+                           const jp_obrs_params *prm, const jp_obrs_outputs *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Gradient of the on-policy distillation term of Sec. 4.2 (3), Eq. distill_loss, with respect to

@@ -52,6 +52,8 @@ jp_status check_params(const jp_obrs_params *prm, int64_t V, bool need_clips)
     if (prm->flags & ~KNOWN_FLAGS) return JP_ERR_UNSUPPORTED;
     if (!(prm->lambda > 0.f) || !isfinite(prm->lambda)) return JP_ERR_PARAM;
     if (need_clips && (!(prm->c1 > 0.f) || !(prm->c2 > 0.f))) return JP_ERR_PARAM;
+    if (prm->f_mode > JP_F_BAND) return JP_ERR_UNSUPPORTED;
+    if (prm->f_mode == JP_F_BAND && !(prm->f_lo >= 0.f && prm->f_lo <= prm->f_hi)) return JP_ERR_PARAM;
     if (prm->k < 1 || (int64_t)prm->k > V) return JP_ERR_PARAM;
     if (prm->k > JP_K_MAX) return JP_ERR_UNSUPPORTED;
     return JP_OK;
@@ -121,6 +123,8 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
     if (T < 0 || T > 0x7fffffffLL) return JP_ERR_SHAPE;
     if (prm->flags & ~KNOWN_FLAGS) return JP_ERR_UNSUPPORTED;
     if (!(prm->lambda > 0.f) || !isfinite(prm->lambda) || !(prm->c1 > 0.f) || !(prm->c2 > 0.f)) return JP_ERR_PARAM;
+    if (prm->f_mode > JP_F_BAND) return JP_ERR_UNSUPPORTED;
+    if (prm->f_mode == JP_F_BAND && !(prm->f_lo >= 0.f && prm->f_lo <= prm->f_hi)) return JP_ERR_PARAM;
     const Workspace w = carve(workspace, T);
     if (!workspace || workspace_bytes < w.bytes) return JP_ERR_WORKSPACE;
     if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
@@ -137,6 +141,7 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
     f.ref_logprob = ref_logprob;
     f.kl = (prm->flags & JP_FLAG_DISTILL_KL) ? (out->distill_kl ? out->distill_kl : w.kl) : nullptr;
     f.lambda = prm->lambda; f.c1 = prm->c1; f.c2 = prm->c2;
+    f.f_mode = (int)prm->f_mode; f.f_lo = prm->f_lo; f.f_hi = prm->f_hi;
     f.alpha_expected = ((prm->flags & JP_FLAG_ALPHA_EXPECTED) || !have_uniforms) ? 1 : 0;
     f.stats = out->stats ? out->stats : w.stats;
     f.w = out->w_obrs; f.rho = out->rho;
@@ -338,6 +343,54 @@ jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V
                          uniforms != nullptr);
 }
 
+jp_status jp_obrs_token_logprob(const void *logits, int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                                const int32_t *sampled_ids, float *out_logprob, void *stream)
+{
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s != JP_OK) return s;
+    if (T > 0 && (!logits || !sampled_ids || !out_logprob)) return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(logits) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    jp::LogprobArgs a{logits, T, V, row_stride, sampled_ids, out_logprob};
+    if (jp::launch_token_logprob(a, (int)dt, (hipStream_t)stream) != hipSuccess) return JP_ERR_HIP;
+    return JP_OK;
+}
+
+size_t jp_obrs_forward3_workspace_bytes(int64_t T, int64_t V, int32_t k, jp_dtype dt, uint32_t flags)
+{
+    const size_t base = jp_obrs_workspace_bytes(T, V, k, dt, flags);
+    return base ? base + round_up((size_t)T * 4) : 0;
+}
+
+jp_status jp_obrs_forward3(const void *actor_logits, const void *policy_new_logits, const void *policy_ref_logits,
+                           int32_t target_is_ref, int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                           const int32_t *sampled_ids, const float *uniforms, const jp_obrs_params *prm,
+                           const jp_obrs_outputs *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!prm || !out) return JP_ERR_NULL;
+    if (T > 0 && !policy_ref_logits) return JP_ERR_NULL;
+    if (target_is_ref)
+        return jp_obrs_forward(actor_logits, policy_ref_logits, T, V, row_stride, dt, sampled_ids, uniforms,
+                               nullptr, prm, out, workspace, workspace_bytes, stream);
+    const size_t base = jp_obrs_workspace_bytes(T, V, prm->k, dt, prm->flags);
+    if (base == 0) return JP_ERR_SHAPE;
+    if (!workspace || workspace_bytes < base + round_up((size_t)(T > 0 ? T : 0) * 4)) return JP_ERR_WORKSPACE;
+    float *ref_lp = (float *)((char *)workspace + base);
+    // argument errors of the main call are reported before anything is launched
+    if (T > 0 && (!actor_logits || !policy_new_logits || !sampled_ids)) return JP_ERR_NULL;
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s == JP_OK) s = check_params(prm, V, true);
+    if (s != JP_OK) return s;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(actor_logits) || !aligned16(policy_new_logits) || !aligned16(policy_ref_logits) ||
+        ((size_t)row_stride * esz) % 16 != 0 || ((uintptr_t)workspace & (ALIGN - 1)) != 0)
+        return JP_ERR_ALIGN;
+    s = jp_obrs_token_logprob(policy_ref_logits, T, V, row_stride, dt, sampled_ids, ref_lp, stream);
+    if (s != JP_OK) return s;
+    return jp_obrs_forward(actor_logits, policy_new_logits, T, V, row_stride, dt, sampled_ids, uniforms,
+                           ref_lp, prm, out, workspace, base, stream);
+}
+
 /* Gradient of the distillation term with respect to the actor logits (second streaming pass). */
 jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
                                int64_t row_stride, jp_dtype dt, const float *row_scale, float scale,
@@ -381,6 +434,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 4; }
+int jp_obrs_abi_version(void) { return 5; }
 
 }  // extern "C"

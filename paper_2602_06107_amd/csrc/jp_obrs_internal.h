@@ -71,6 +71,8 @@ struct FinalizeArgs {
     const float *accept, *zapprox, *zexact, *logratio, *logp, *ref_logprob;
     const float *kl;                  // nullptr unless the distillation term was requested
     float lambda, c1, c2;
+    int f_mode;                       // JP_F_*
+    float f_lo, f_hi;
     int alpha_expected;
     jp_obrs_stats *stats;
     float *w, *rho;
@@ -88,6 +90,14 @@ struct GradArgs {
     uint32_t seg_batches, segs;       // set by the launcher: batches of 1024 chunks per workgroup, workgroups per row
 };
 
+struct LogprobArgs {
+    const void *logits;               // [T, V]
+    int64_t T, V, stride;
+    const int32_t *ids;               // [T]
+    float *out;                       // [T]
+};
+
+hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st);   // a.actor unused
 hipError_t launch_distill_grad(const GradArgs &a, int dtype, int grad_dtype, hipStream_t st);

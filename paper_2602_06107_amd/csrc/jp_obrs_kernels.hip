@@ -1001,6 +1001,78 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
 }
 
 // =================================================================================================
+// log softmax(l_t)[x_t] for one logit tensor: how log p_ref(a_t) of Alg. 1 (Phase 2, step 1) is read
+// off a third tensor.  One wavefront per row, one sweep: per-lane exponent reference (moved only
+// when a chunk maximum exceeds it by the margin) and sum, combined across the wave at the end.
+// =================================================================================================
+template <class ET>
+__global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
+{
+    constexpr int VEC = ET::VEC;
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int x = A.ids[t];
+    const int64_t V = A.V;
+    if (x < 0 || x >= V) {
+        if (lane == 0) A.out[t] = x < 0 ? 0.f : __uint_as_float(0x7fc00000u);
+        return;
+    }
+    const char *row = (const char *)A.logits + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const gvec_ptr v = as_global_vec(row);
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
+    const uint32_t nit = nfull / WAVE;
+    float M2 = M2_UNSET, mthr = -2.0e38f, s = 0.f;
+    auto consume = [&](const float (&f)[VEC], bool valid) {
+        const float m = max_of<VEC>(f);
+        if (valid && m > mthr) {                                    // rare: move this lane's reference
+            const float newM2 = m * LOG2E_F;
+            s *= __builtin_amdgcn_exp2f(M2 - newM2);
+            M2 = newM2;
+            mthr = m + RESCALE_MARGIN2 / LOG2E_F;
+        }
+        if (valid) s += sum_exp2<VEC>(f, M2);
+    };
+    if (nit > 0) {
+        constexpr int D = 4;
+        const uint32_t last = nit - 1;
+        u32x4 w[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) w[d] = stream_load(v + (((uint32_t)d < last ? (uint32_t)d : last) * WAVE + lane));
+        for (uint32_t it = 0; it < nit; it += D) {
+            u32x4 c[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) c[d] = w[d];
+#pragma unroll
+            for (int d = 0; d < D; ++d) w[d] = stream_load(v + ((it + D + d < last ? it + D + d : last) * WAVE + lane));
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (d == 0 || it + d < nit) {
+                    float f[VEC];
+                    ET::unpack(c[d], f);
+                    consume(f, true);
+                }
+            }
+        }
+    }
+    {
+        const uint32_t c = nit * WAVE + lane;
+        if (c < nchunks) {
+            float f[VEC];
+            load_chunk<ET>(row, c, nfull, tail, f);
+            consume(f, true);
+        }
+    }
+    // combine the 64 (reference, sum) pairs: common reference = the largest, sums rescaled to it
+    const float Mw = uniform_f(wave_max(M2));
+    const double S = wave_sum(M2 == M2_UNSET ? 0.0 : (double)(s * __builtin_amdgcn_exp2f(M2 - Mw)));
+    const double lse = ((double)Mw + log2_of_sum(S)) * LN2_D;
+    const double lp = (double)ET::load1(row, x) - lse;
+    if (lane == 0) A.out[t] = isfinite(lse) ? (float)lp : __uint_as_float(0x7fc00000u);
+}
+
+// =================================================================================================
 // Gradient of the distillation term KL(SG(p) || q) of Sec. 4.2 (3) with respect to the actor
 // logits: g_t[v] = w_t (q_t(v) - p_t(v)), q = 2^(lq log2e - LSEq log2e), p likewise.  A second
 // streaming pass: reads both logit rows once, writes one row.  A workgroup of 256 threads covers
@@ -1211,7 +1283,10 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
             const double zt = kappa * (double)zap;
             const double ratio = (double)__builtin_amdgcn_exp2f(lr * LOG2E_F);      // p(x)/q(x)
             const double wd = zt * (lam > ratio ? lam : ratio);
+            // F(w): truncation (Alg. 1 step 3), identity, or two-sided truncation (Sec. 2)
             double rd = wd < (double)A.c1 ? wd : (double)A.c1;
+            if (A.f_mode == JP_F_IDENTITY) rd = wd;
+            else if (A.f_mode == JP_F_BAND) rd = (wd >= (double)A.f_lo && wd <= (double)A.f_hi) ? wd : 0.0;
             if (A.ref_logprob) {
                 const double rr = (double)__builtin_amdgcn_exp2f(refdiff * LOG2E_F); // p_ref(x)/p(x)
                 rd *= rr < (double)A.c2 ? rr : (double)A.c2;
@@ -1308,6 +1383,15 @@ hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
     int64_t blocks = (a.T + FINALIZE_THREADS - 1) / FINALIZE_THREADS;
     blocks = blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
     hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)blocks), dim3(FINALIZE_THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (dtype == JP_BF16) hipLaunchKernelGGL((token_logprob_kernel<Bf16Elem>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((token_logprob_kernel<F32Elem>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

@@ -21,18 +21,20 @@ JP_F32, JP_BF16 = 0, 1
 JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED, JP_FLAG_DISTILL_KL = 1, 2, 4, 8
 JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
 JP_TAIL_DROP, JP_TAIL_KTH, JP_TAIL_REST = 0, 1, 2
+JP_F_TRUNCATE, JP_F_IDENTITY, JP_F_BAND = 0, 1, 2
 (JP_OK, JP_ERR_NULL, JP_ERR_SHAPE, JP_ERR_PARAM, JP_ERR_ALIGN, JP_ERR_WORKSPACE,
  JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
 
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
            "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
-           "jp_obrs_forward_stored",
+           "jp_obrs_forward_stored", "jp_obrs_token_logprob", "jp_obrs_forward3",
+           "jp_obrs_forward3_workspace_bytes",
            "jp_status_string", "jp_obrs_abi_version")
 
 
 class Params(C.Structure):
     _fields_ = [("lambda_", C.c_float), ("k", C.c_int32), ("c1", C.c_float), ("c2", C.c_float),
-                ("flags", C.c_uint32)]
+                ("flags", C.c_uint32), ("f_mode", C.c_uint32), ("f_lo", C.c_float), ("f_hi", C.c_float)]
 
 
 class Stats(C.Structure):
@@ -86,6 +88,15 @@ _lib.jp_obrs_forward_stored.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_in
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(Params), C.c_int, C.POINTER(Outputs), C.c_void_p,
                                         C.c_size_t, C.c_void_p]
+_lib.jp_obrs_token_logprob.restype = C.c_int
+_lib.jp_obrs_token_logprob.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
+                                       C.c_void_p, C.c_void_p]
+_lib.jp_obrs_forward3_workspace_bytes.restype = C.c_size_t
+_lib.jp_obrs_forward3_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int, C.c_uint32]
+_lib.jp_obrs_forward3.restype = C.c_int
+_lib.jp_obrs_forward3.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                  C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(Params),
+                                  C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -191,14 +202,53 @@ def _logit_args(actor: torch.Tensor, policy: torch.Tensor):
     return T, V, actor.stride(0) if T > 1 else max(actor.stride(0), V), _dtype_code(actor)
 
 
+def _params(lam, k, c1, c2, flags, adjust=None) -> Params:
+    """``adjust``: None (the paper's truncation min(w, c1)) or (JP_F_* mode, lo, hi)."""
+    mode, lo, hi = (JP_F_TRUNCATE, 0.0, 0.0) if adjust is None else adjust
+    return Params(float(lam), int(k), float(c1), float(c2), int(flags), int(mode), float(lo), float(hi))
+
+
 def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c1, c2, flags,
-                    buf: Buffers, stream=None) -> None:
+                    buf: Buffers, stream=None, adjust=None) -> None:
     """Whole hot path on ``stream`` (default: torch's current stream).  Raises JpError on failure."""
     T, V, stride, dt = _logit_args(actor, policy)
-    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    prm = _params(lam, k, c1, c2, flags, adjust)
     st = _lib.jp_obrs_forward(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
                               _p(ref_logprob), C.byref(prm), C.byref(buf.out), _p(buf.workspace),
                               buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_token_logprob(logits, sampled_ids, out=None, stream=None):
+    """log softmax(logits[t])[sampled_ids[t]] per row -> float32 [T] (allocated with torch if not given)."""
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be a [T, V] tensor with contiguous rows")
+    T, V = logits.shape
+    stride = logits.stride(0) if T > 1 else max(logits.stride(0), V)
+    if out is None:
+        out = torch.empty(T, dtype=torch.float32, device=logits.device)
+    st = _lib.jp_obrs_token_logprob(_p(logits), T, V, stride, _dtype_code(logits), _p(sampled_ids), _p(out),
+                                    _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+    return out
+
+
+def jp_obrs_forward3_workspace_bytes(T: int, V: int, k: int, dt: int, flags: int = 0) -> int:
+    return _lib.jp_obrs_forward3_workspace_bytes(T, V, k, dt, flags)
+
+
+def jp_obrs_forward3(actor, policy_new, policy_ref, target_is_ref, sampled_ids, uniforms, lam, k, c1, c2,
+                     flags, buf: Buffers, stream=None, adjust=None) -> None:
+    """Three-distribution form: p_inf, p_new, p_ref as separate tensors, target selectable."""
+    T, V, stride, dt = _logit_args(actor, policy_ref)
+    if policy_new is not None:
+        _logit_args(actor, policy_new)
+    prm = _params(lam, k, c1, c2, flags, adjust)
+    st = _lib.jp_obrs_forward3(_p(actor), _p(policy_new), _p(policy_ref), int(bool(target_is_ref)), T, V,
+                               stride, dt, _p(sampled_ids), _p(uniforms), C.byref(prm), C.byref(buf.out),
+                               _p(buf.workspace), buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 
@@ -249,8 +299,9 @@ def jp_obrs_rows(actor, policy, sampled_ids, uniforms, lam, k, flags, buf: Buffe
         raise JpError(st)
 
 
-def jp_obrs_finalize(T, sampled_ids, ref_logprob, lam, k, c1, c2, flags, buf: Buffers, stream=None) -> None:
-    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+def jp_obrs_finalize(T, sampled_ids, ref_logprob, lam, k, c1, c2, flags, buf: Buffers, stream=None,
+                     adjust=None) -> None:
+    prm = _params(lam, k, c1, c2, flags, adjust)
     st = _lib.jp_obrs_finalize(int(T), _p(sampled_ids), _p(ref_logprob), C.byref(prm), C.byref(buf.out),
                                _p(buf.workspace), buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:

@@ -27,11 +27,11 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert set(obrs.EXPORTS) == set(names)
-    assert obrs.jp_obrs_abi_version() == 4
+    assert obrs.jp_obrs_abi_version() == 5
 
 
 def test_struct_layouts_match_header():
-    assert C.sizeof(obrs.Params) == 20
+    assert C.sizeof(obrs.Params) == 32
     assert C.sizeof(obrs.Stats) == 72
     assert C.sizeof(obrs.Outputs) == 16 * C.sizeof(C.c_void_p)
 
@@ -46,12 +46,12 @@ def test_workspace_bytes():
 
 def _call(actor=0x10000, policy=0x20000, T=4, V=1024, stride=1024, dt=None, ids=0x30000, uni=0x40000,
           ref=None, lam=1.0, k=8, c1=3.0, c2=3.0, flags=0, ws=0x100000, ws_bytes=1 << 20, out=None,
-          prm_null=False):
+          prm_null=False, f_mode=0, f_lo=0.0, f_hi=0.0):
     """Calls jp_obrs_forward with fake (never dereferenced) device addresses: every case below must
     be rejected by host-side validation, so nothing is launched."""
     lib = obrs.raw()
     dt = obrs.JP_F32 if dt is None else dt
-    prm = obrs.Params(lam, k, c1, c2, flags)
+    prm = obrs.Params(lam, k, c1, c2, flags, f_mode, f_lo, f_hi)
     o = obrs.Outputs() if out is None else out
     return lib.jp_obrs_forward(actor, policy, T, V, stride, dt, ids, uni, ref,
                                None if prm_null else C.byref(prm), C.byref(o), ws, ws_bytes, None)
@@ -74,6 +74,9 @@ def _call(actor=0x10000, policy=0x20000, T=4, V=1024, stride=1024, dt=None, ids=
     (dict(lam=float("inf")), obrs.JP_ERR_PARAM),
     (dict(c1=0.0), obrs.JP_ERR_PARAM),
     (dict(c2=float("nan")), obrs.JP_ERR_PARAM),
+    (dict(f_mode=3), obrs.JP_ERR_UNSUPPORTED),
+    (dict(f_mode=2, f_lo=2.0, f_hi=1.0), obrs.JP_ERR_PARAM),
+    (dict(f_mode=2, f_lo=-1.0, f_hi=1.0), obrs.JP_ERR_PARAM),
     (dict(k=0), obrs.JP_ERR_PARAM),
     (dict(k=2000), obrs.JP_ERR_PARAM),             # k > V
     (dict(k=257), obrs.JP_ERR_UNSUPPORTED),        # k > JP_K_MAX

@@ -1,0 +1,121 @@
+"""GPU parity of the three-distribution form (Eq. obrs_ppo, Alg. 1: p_inf, p_new, p_ref as separate
+tensors), of jp_obrs_token_logprob and of the adjustment functions F of Sec. 2, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from oracle import obrs_oracle as orc
+    from paper_2602_06107_amd import obrs
+    from paper_2602_06107_amd import workloads as wl
+    import parity_util as pu
+
+DEV = "cuda"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [8, 37, 255, 515, 4100, 33333, 151936])
+def test_token_logprob(dtype, V):
+    T = 11
+    _say(f"token log-prob: {dtype} T={T} V={V}, padded stride, padding row, bad id, -inf entries")
+    esz = 2 if dtype == torch.bfloat16 else 4
+    stride = (V * esz + 15) // 16 * 16 // esz + 16 // esz * 2
+    w = wl.make_logits(T, V, dtype, seed=55 + V, device=DEV, actor_sigma=3.0, spikes=min(3, V),
+                       pad_every=4, row_stride=stride)
+    w.sampled_ids[5] = V                             # outside the vocabulary
+    w.policy[2, : V // 2] = float("-inf")            # masked entries
+    x = w.sampled_ids
+    x[2] = V - 1
+    got = obrs.jp_obrs_token_logprob(w.policy, x).cpu().numpy().astype(np.float64)
+    want = orc.token_logprob(wl.logits_to_numpy(w.policy), x.cpu().numpy())
+    tol = pu.TOL[dtype]
+    xs = x.cpu().numpy()
+    assert np.all(got[xs < 0] == 0.0)
+    assert np.all(np.isnan(got[xs >= V])) and np.all(np.isnan(want[xs >= V]))
+    ok = (xs >= 0) & (xs < V)
+    pu._close(got[ok], want[ok], 0.0, "log p(x)", abs_tol=tol)
+
+
+def _adjust_cases():
+    return [None, (obrs.JP_F_IDENTITY, 0.0, 0.0), (obrs.JP_F_BAND, 0.5, 2.0), (obrs.JP_F_BAND, 0.0, 1e30)]
+
+
+@pytest.mark.parametrize("adjust", _adjust_cases())
+def test_adjustment_functions(adjust):
+    _say(f"F variants: bf16 T=512 V=20000 adjust={adjust}")
+    w = wl.make_logits(512, 20000, torch.bfloat16, seed=31, device=DEV).with_params(k=32, lam=1.0, c1=1.2)
+    w.ref_logprob = -torch.rand(w.T, device=DEV) * 3.0
+    T, V = w.T, w.V
+    buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_BF16, 0, DEV)
+    obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, w.ref_logprob, w.lam, w.k, w.c1,
+                         w.c2, 0, buf, adjust=adjust)
+    torch.cuda.synchronize()
+    R = pu.run_oracle(w)
+    g, band = pu.check_rows(buf, w, R)
+    mask = np.where(R.out["valid"] == 1, g["mask"], 0).astype(np.int32)
+    mode, lo, hi = (orc.F_TRUNCATE, 0.0, 0.0) if adjust is None else adjust
+    ref = w.ref_logprob.cpu().numpy().astype(np.float64)
+    b, w_want, rho_want = orc.batch_f(R.out, mask, w.lam, mode, w.c1, lo, hi, w.c2, ref)
+    tol = pu.TOL[torch.bfloat16]
+    pu._close(g["w_obrs"], w_want, tol, "w_OBRS")
+    sure = np.ones(T, dtype=bool)
+    if mode == orc.F_BAND:                                    # either side of a band edge is valid within tolerance
+        sure = (np.abs(w_want - lo) > 2 * tol * np.maximum(lo, 1e-30)) & (np.abs(w_want - hi) > 2 * tol * hi)
+        assert sure.sum() > T // 2
+        assert (rho_want[sure] == 0).any() and (rho_want[sure] > 0).any() or hi > 1e20
+    pu._close(g["rho"][sure], rho_want[sure], tol, "rho")
+
+
+@pytest.mark.parametrize("target_is_ref", [0, 1])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_three_distribution_form(dtype, target_is_ref):
+    T, V, k = 48, 30011 if dtype == torch.float32 else 151936, 32
+    if dtype == torch.float32:
+        V = 30012                                             # fp32 row pitch must be a multiple of 16 bytes
+    _say(f"three distributions: {dtype} T={T} V={V} target={'ref' if target_is_ref else 'new'}")
+    w = wl.make_logits(T, V, dtype, seed=91, device=DEV, noise_sigma=0.8, pad_every=7).with_params(k=k, lam=1.1)
+    g = torch.Generator(device=DEV); g.manual_seed(17)
+    p_new = w.policy
+    p_ref = (w.policy.float() + 0.3 * torch.randn(w.policy.shape, generator=g, device=DEV)).to(dtype)
+    flags = obrs.JP_FLAG_TOPK_LOGPROBS
+    nbytes = obrs.jp_obrs_forward3_workspace_bytes(T, V, k, obrs._dtype_code(w.actor), flags)
+    buf = obrs.alloc_buffers(T, V, k, obrs._dtype_code(w.actor), flags, DEV, workspace_bytes=nbytes)
+    obrs.jp_obrs_forward3(w.actor, p_new, p_ref, target_is_ref, w.sampled_ids, w.uniforms, w.lam, k, w.c1,
+                          w.c2, flags, buf)
+    torch.cuda.synchronize()
+    # the oracle's statement of the same thing: two-tensor rows on (p_inf, p_target), and the
+    # p_ref / p_target factor from the third tensor's token log-probabilities
+    target = p_ref if target_is_ref else p_new
+    wt = w.with_params(policy=target)
+    R = pu.run_oracle(wt)
+    if target_is_ref:
+        wt.ref_logprob = None
+    else:
+        lp_ref = orc.token_logprob(wl.logits_to_numpy(p_ref), w.sampled_ids.cpu().numpy())
+        wt.ref_logprob = torch.as_tensor(np.nan_to_num(lp_ref), dtype=torch.float32, device=DEV)
+    gg, band = pu.check_rows(buf, wt, R, flags=flags)
+    pu.check_batch(buf, wt, R, gg, flags=flags)
+
+
+def test_three_distribution_bad_arguments():
+    _say("three distributions: host-side validation")
+    w = wl.tiny(DEV)
+    T, V, k = w.T, w.V, w.k
+    nbytes = obrs.jp_obrs_forward3_workspace_bytes(T, V, k, obrs.JP_F32, 0)
+    assert nbytes == obrs.jp_obrs_workspace_bytes(T, V, k, obrs.JP_F32, 0) + 256
+    buf = obrs.alloc_buffers(T, V, k, obrs.JP_F32, 0, DEV)          # too small for target = new
+    with pytest.raises(obrs.JpError) as e:
+        obrs.jp_obrs_forward3(w.actor, w.policy, w.policy, 0, w.sampled_ids, w.uniforms, 1.0, k, 3.0, 3.0, 0, buf)
+    assert e.value.status == obrs.JP_ERR_WORKSPACE
+    obrs.jp_obrs_forward3(w.actor, None, w.policy, 1, w.sampled_ids, w.uniforms, 1.0, k, 3.0, 3.0, 0, buf)
+    with pytest.raises(obrs.JpError) as e:
+        obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, None, 1.0, k, 3.0, 3.0, 0, buf,
+                             adjust=(7, 0.0, 1.0))
+    assert e.value.status == obrs.JP_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
