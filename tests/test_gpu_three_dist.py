@@ -43,7 +43,8 @@ def test_token_logprob(dtype, V):
 
 
 def _adjust_cases():
-    return [None, (obrs.JP_F_IDENTITY, 0.0, 0.0), (obrs.JP_F_BAND, 0.5, 2.0), (obrs.JP_F_BAND, 0.0, 1e30)]
+    # (JP_F_* mode, lo, hi): 1 = identity, 2 = band; None = the default truncation
+    return [None, (1, 0.0, 0.0), (2, 0.5, 2.0), (2, 0.0, 1e30)]
 
 
 @pytest.mark.parametrize("adjust", _adjust_cases())
