@@ -421,6 +421,76 @@ void jpo_distill_grad(const void *actor, const void *policy, int dtype, int64_t 
  * Z_t = kappa Z_approx;  w = Z_t max(lambda, p(x)/q(x));
  * rho = min(w, c1) * min(p_ref(x)/p(x), c2)   (second factor 1 if no ref).
  * use_expected_alpha != 0 replaces alpha_hat by the mean of a(x).        */
+/* ---- the scaling factor for a given acceptance budget (Sec. 3.3, Theorem 2) -----------------
+ * For a budget abar in (0, 1] there is a lambda with sum_v q_v min(1, p_v / (lambda q_v)) = abar.
+ * The left side is Z(lambda) = sum_{r_v > lambda} q_v + (1/lambda) sum_{r_v <= lambda} p_v with
+ * r_v = p_v / q_v: continuous, equal to 1 up to min_v r_v, strictly decreasing after it, and
+ * piecewise of the form A + B / lambda between consecutive ratios.  So: sort the ratios, find the
+ * piece on which Z crosses abar, solve A + B / lambda = abar there.  For abar = 1 every
+ * lambda <= min r_v does; the largest of them is returned (lambda = sup{ l : Z(l) >= abar }).
+ * Tokens with q_v = 0 or p_v = 0 keep nothing whatever lambda is and are left out.
+ * Returns NaN for abar outside (0, 1].                                                         */
+typedef struct { double r, q, p; } jpo_ratio;
+
+static int cmp_ratio(const void *a, const void *b)
+{
+    double ra = ((const jpo_ratio *)a)->r, rb = ((const jpo_ratio *)b)->r;
+    return (ra > rb) - (ra < rb);
+}
+
+double jpo_lambda_for_budget(const double *lq, const double *lp, int64_t V, double abar)
+{
+    if (!(abar > 0.0) || abar > 1.0) return NAN;
+    double lse_q = jpo_logsumexp(lq, V), lse_p = jpo_logsumexp(lp, V);
+    jpo_ratio *e = (jpo_ratio *)malloc((size_t)V * sizeof(jpo_ratio));
+    int64_t n = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        double q = exp(lq[v] - lse_q), p = exp(lp[v] - lse_p);
+        if (!(q > 0.0) || !(p > 0.0)) continue;
+        e[n].r = exp((lp[v] - lse_p) - (lq[v] - lse_q));
+        e[n].q = q;
+        e[n].p = p;
+        ++n;
+    }
+    qsort(e, (size_t)n, sizeof(jpo_ratio), cmp_ratio);
+    /* A = mass of q on ratios above the piece, B = mass of p on ratios at or below it */
+    double A = 0.0, B = 0.0, lambda = NAN;
+    for (int64_t i = 0; i < n; ++i) A += e[i].q;
+    if (n == 0) { free(e); return NAN; }
+    /* piece 0 is lambda <= r_(1): Z = A (all of q that can be kept); it holds the budget only if abar >= A */
+    if (abar >= A) { lambda = e[0].r; free(e); return lambda; }
+    for (int64_t i = 0; i < n; ++i) {
+        A -= e[i].q;
+        B += e[i].p;
+        /* piece i+1: r_(i+1) <= lambda < r_(i+2) (the last piece is unbounded above) */
+        double upper = (i + 1 < n) ? e[i + 1].r : INFINITY;
+        double z_upper = (i + 1 < n) ? A + B / upper : 0.0;
+        if (abar > z_upper || i + 1 == n) {
+            lambda = B / (abar - A);
+            break;
+        }
+    }
+    free(e);
+    return lambda;
+}
+
+void jpo_lambda_for_budget_rows(const void *actor, const void *policy, int dtype, int64_t T, int64_t V,
+                                int64_t row_stride, const int32_t *x, const float *row_target,
+                                double target, double *out)
+{
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    double *lq = (double *)malloc((size_t)V * sizeof(double));
+    double *lp = (double *)malloc((size_t)V * sizeof(double));
+    for (int64_t t = 0; t < T; ++t) {
+        if (x[t] < 0) { out[t] = 0.0; continue; }
+        jpo_widen_row((const char *)actor + (size_t)t * (size_t)row_stride * esz, dtype, V, lq);
+        jpo_widen_row((const char *)policy + (size_t)t * (size_t)row_stride * esz, dtype, V, lp);
+        out[t] = jpo_lambda_for_budget(lq, lp, V, row_target ? (double)row_target[t] : target);
+    }
+    free(lp);
+    free(lq);
+}
+
 /* The adjustment function F of the importance weight (Sec. 2, related work; Eq. obrs_ppo applies it
  * to p_target / p'_inf):  0 = truncation F(w) = min(w, c1) (TIS; the paper's choice, Alg. 1 step 3),
  * 1 = identity F(w) = w,  2 = two-sided truncation F(w) = w if lo <= w <= hi, else 0.             */

@@ -107,6 +107,11 @@ def lib():
         l.jpo_token_logprob.restype = None
         l.jpo_token_logprob.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p,
                                         C.c_void_p]
+        l.jpo_lambda_for_budget.restype = C.c_double
+        l.jpo_lambda_for_budget.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_double]
+        l.jpo_lambda_for_budget_rows.restype = None
+        l.jpo_lambda_for_budget_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64,
+                                                 C.c_int64, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
         l.jpo_max_threads.restype = C.c_int
         l.jpo_widen_row.restype = None
         l.jpo_widen_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
@@ -204,6 +209,25 @@ def batch(rows_out: np.ndarray, mask, lam: float, c1: float, c2: float, ref_logp
     lib().jpo_batch(_ptr(rows_out), _ptr(mask), T, float(lam), float(c1), float(c2), _ptr(ref),
                     int(use_expected_alpha), C.byref(b), _ptr(w), _ptr(rho))
     return b, w, rho
+
+
+def lambda_for_budget(lq, lp, abar: float) -> float:
+    """The lambda whose OBRS rule accepts exactly the fraction ``abar`` (Sec. 3.3, Theorem 2)."""
+    lq, lp = _f64(lq), _f64(lp)
+    return lib().jpo_lambda_for_budget(_ptr(lq), _ptr(lp), lq.size, float(abar))
+
+
+def lambda_for_budget_rows(actor: np.ndarray, policy: np.ndarray, x, target: float, row_target=None):
+    """Per-row lambdas for a batch stored as float32 / float64 / bf16 bits -> float64 [T]."""
+    assert actor.shape == policy.shape and actor.ndim == 2 and actor.dtype == policy.dtype
+    a, code = storage_view(actor)
+    T, V = a.shape
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    rt = None if row_target is None else np.ascontiguousarray(row_target, dtype=np.float32)
+    out = np.empty(T, dtype=np.float64)
+    lib().jpo_lambda_for_budget_rows(_ptr(a), _ptr(policy), code, T, V, a.strides[0] // a.itemsize,
+                                     _ptr(x), _ptr(rt), float(target), _ptr(out))
+    return out
 
 
 F_TRUNCATE, F_IDENTITY, F_BAND = 0, 1, 2

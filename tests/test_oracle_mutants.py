@@ -57,6 +57,12 @@ MUTANTS = [
      "if (f_mode == JPO_F_IDENTITY) return w;", "if (f_mode == JPO_F_IDENTITY) return w < c1 ? w : c1;"),
     ("token log-probability forgets the log-sum-exp",
      "out[t] = l[x[t]] - jpo_logsumexp(l, V);", "out[t] = l[x[t]];"),
+    ("budget solver: solves A + B lambda = abar instead of A + B / lambda",
+     "lambda = B / (abar - A);", "lambda = (abar - A) / B;"),
+    ("budget solver: keeps the mass of q at or below the piece in A",
+     "A -= e[i].q;\n        B += e[i].p;", "B += e[i].p;"),
+    ("budget solver: budget 1 returns the largest ratio",
+     "if (abar >= A) { lambda = e[0].r; free(e); return lambda; }", "if (abar >= A) { lambda = e[n - 1].r; free(e); return lambda; }"),
     ("distillation gradient has the wrong sign",
      "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
     ("distillation gradient drops the row weight",

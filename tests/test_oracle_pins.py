@@ -639,3 +639,70 @@ def test_token_logprob_against_scipy_log_softmax():
     wide = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
     gb = orc.token_logprob(bits, np.full(T, 3, np.int32))
     np.testing.assert_allclose(gb, scipy.special.log_softmax(wide, axis=1)[:, 3], atol=1e-13)
+
+
+# ---- the scaling factor for an acceptance budget (Sec. 3.3, Theorem 2) ------------------------------
+
+def _z_of_lambda(q, p, lam):
+    return float(np.minimum(q, p / lam).sum())
+
+
+def test_lambda_for_budget_against_bisection_and_closed_forms():
+    rng = np.random.default_rng(555)
+    V = 200
+    lq = _rand_logits(rng, V)
+    lp = lq + rng.normal(0, 1.2, V)
+    q, p = _softmax64(lq), _softmax64(lp)
+    prev = None
+    for abar in (0.999, 0.9, 0.5, 0.2, 0.05, 0.001):
+        lam = orc.lambda_for_budget(lq, lp, abar)
+        assert _z_of_lambda(q, p, lam) == pytest.approx(abar, rel=1e-12)        # the budget is met exactly
+        lo, hi = 1e-12, 1e12                                                     # plain bisection on Z
+        for _ in range(200):
+            mid = math.sqrt(lo * hi)
+            lo, hi = (mid, hi) if _z_of_lambda(q, p, mid) > abar else (lo, mid)
+        assert lam == pytest.approx(math.sqrt(lo * hi), rel=1e-9)
+        qt, z = orc.post_rejection(lq, lp, lam)                                  # and through Eq. obrs_dist
+        assert z == pytest.approx(abar, rel=1e-12)
+        assert prev is None or lam > prev                                        # smaller budget, larger lambda
+        prev = lam
+    # budget 1: the largest lambda that still accepts everything is min_v p/q
+    assert orc.lambda_for_budget(lq, lp, 1.0) == pytest.approx(float((p / q).min()), rel=1e-12)
+    # p == q: Z(lambda) = min(1, 1/lambda)
+    assert orc.lambda_for_budget(lq, lq, 0.25) == pytest.approx(4.0, rel=1e-12)
+    assert orc.lambda_for_budget(lq, lq, 1.0) == pytest.approx(1.0, rel=1e-12)
+    # beyond the largest ratio Z = 1/lambda
+    tiny = 0.5 / float((p / q).max())
+    assert orc.lambda_for_budget(lq, lp, tiny) == pytest.approx(1.0 / tiny, rel=1e-12)
+    # two tokens by hand: q = (.5, .5), p = (.8, .2): Z = .5 + .2/lambda on [0.4, 1.6] -> abar = .7 at lambda = 1
+    l2q, l2p = np.log([0.5, 0.5]), np.log([0.8, 0.2])
+    assert orc.lambda_for_budget(l2q, l2p, 0.7) == pytest.approx(1.0, rel=1e-13)
+    assert orc.lambda_for_budget(l2q, l2p, 0.5) == pytest.approx(2.0, rel=1e-13)   # Z = 1/lambda beyond 1.6
+    assert orc.lambda_for_budget(l2q, l2p, 0.9) == pytest.approx(0.5, rel=1e-13)   # .5 + .2/.5
+    for bad in (0.0, -0.1, 1.0001, float("nan")):
+        assert math.isnan(orc.lambda_for_budget(lq, lp, bad))
+    # masked entries take no part
+    lq2, lp2 = lq.copy(), lp.copy()
+    lq2[:50] = -np.inf
+    lp2[100:120] = -np.inf
+    q2, p2 = _softmax64(lq2), _softmax64(lp2)
+    lam = orc.lambda_for_budget(lq2, lp2, 0.3)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        assert _z_of_lambda(q2, p2, lam) == pytest.approx(0.3, rel=1e-12)
+
+
+def test_lambda_for_budget_rows_driver():
+    rng = np.random.default_rng(556)
+    T, V = 5, 77
+    a = rng.normal(0, 2, (T, V)).astype(np.float32)
+    p = (a + rng.normal(0, 1, (T, V))).astype(np.float32)
+    x = np.array([1, -1, 3, 4, 5], dtype=np.int32)
+    rt = np.array([0.9, 0.5, 0.5, 0.1, 1.0], dtype=np.float32)
+    got = orc.lambda_for_budget_rows(a, p, x, 0.5, rt)
+    got_scalar = orc.lambda_for_budget_rows(a, p, x, 0.5)
+    for t in range(T):
+        if x[t] < 0:
+            assert got[t] == 0.0
+            continue
+        assert got[t] == orc.lambda_for_budget(a[t], p[t], float(rt[t]))
+        assert _z_of_lambda(_softmax64(a[t]), _softmax64(p[t]), got_scalar[t]) == pytest.approx(0.5, rel=1e-12)
