@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--token-logprob", action="store_true",
                     help="also time jp_obrs_token_logprob (log-probability of the sampled token under one "
                          "more logit tensor, one sweep) and report it as \"token_logprob\"")
+    ap.add_argument("--budget", type=float, default=0.0,
+                    help="also time jp_obrs_lambda_for_budget (per-row lambda that meets this acceptance "
+                         "budget, three sweeps) and report it as \"lambda_for_budget\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -233,6 +236,25 @@ def main():
                         "algorithmic_bytes": l_bytes, "bound": "hbm", "achieved": l_bytes / (l_avg * 1e-3) / 1e9,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": l_bytes / (l_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    budget_info = None
+    if args.budget > 0:
+        lam_out = torch.empty(T, dtype=torch.float32, device=dev)
+        bev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(min(args.steps, 5) + 1)]
+        for a, b in bev:
+            a.record()
+            obrs.jp_obrs_lambda_for_budget(w.actor, w.policy, args.budget, buf, out=lam_out)
+            b.record()
+        torch.cuda.synchronize()
+        b_ms = sorted(a.elapsed_time(b) for a, b in bev[1:])
+        b_avg = sum(b_ms) / len(b_ms)
+        b_bytes = 3 * T * 2 * V * esz                      # three sweeps of both rows
+        budget_info = {"kernel": "budget_kernel<bf16>", "abar": args.budget, "kernel_ms_avg": b_avg,
+                       "kernel_ms_min": b_ms[0], "algorithmic_bytes": b_bytes, "bound": "hbm",
+                       "achieved": b_bytes / (b_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": b_bytes / (b_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "mean_lambda": float(lam_out.double().mean())}
+
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)
         for _ in range(args.calibrate_copy):
@@ -287,6 +309,8 @@ def main():
         line["stored_actor"] = stored_info
     if logprob_info is not None:
         line["token_logprob"] = logprob_info
+    if budget_info is not None:
+        line["lambda_for_budget"] = budget_info
     print(json.dumps(line), flush=True)
 
 

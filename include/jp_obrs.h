@@ -241,6 +241,24 @@ jp_status jp_obrs_forward3(const void *actor_logits, const void *policy_new_logi
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The scaling factor for an acceptance budget (Sec. 3.3, Theorem 2): for every row the lambda_t with
+ *   sum_v q_t(v) min(1, p_t(v) / (lambda_t q_t(v))) = abar_t,   abar_t = row_target ? row_target[t] : target,
+ * i.e. the threshold at which the OBRS rule accepts exactly the fraction abar_t of the proposals.
+ * For abar_t = 1 (every lambda up to min_v p/q accepts everything) the largest such lambda is
+ * returned.  Three sweeps of the two logit tensors; the log-sum-exps and the row status come from
+ * `workspace`, where a preceding jp_obrs_rows / jp_obrs_forward call on the SAME tensors and T
+ * left them.  Accuracy: the bracket is narrowed to 128 / 64^3 in log2 lambda and the last step is
+ * the closed form on that piece, so the budget is met to the float tolerance of the other outputs;
+ * lambda itself is only as well determined as the budget determines it (near abar = 1 it is not).
+ *   out_lambda: device [T] fp32; padding rows 0; rows with data errors, or a budget outside (0, 1], NaN.
+ * target is checked on the host (JP_ERR_PARAM) when row_target is NULL.
+ */
+jp_status jp_obrs_lambda_for_budget(const void *actor_logits, const void *policy_logits,
+                                    int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                                    const float *row_target, float target, float *out_lambda,
+                                    const void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gradient of the on-policy distillation term of Sec. 4.2 (3), Eq. distill_loss, with respect to
  * the actor logits.  The term per token is KL(SG(p_t) || q_t) with the target p_t held fixed and
  * q_t = softmax(actor logits), so d/d lq_t[v] = q_t(v) - p_t(v).  This call writes

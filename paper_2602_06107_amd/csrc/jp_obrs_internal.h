@@ -97,6 +97,17 @@ struct LogprobArgs {
     float *out;                       // [T]
 };
 
+struct BudgetArgs {
+    const void *actor, *policy;       // [T, V] logits
+    int64_t T, V, stride;
+    const double *lse_q, *lse_p;      // [T] from the row stage
+    const uint8_t *rowflag;           // [T] from the row stage
+    const float *row_target;          // [T] or nullptr
+    float target;
+    float *lambda_out;                // [T]
+};
+
+hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st);
 hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st);   // a.actor unused

@@ -1073,6 +1073,181 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
 }
 
 // =================================================================================================
+// Scaling factor for an acceptance budget (Sec. 3.3, Theorem 2): per row the lambda with
+// Z(lambda) = sum_v min(q_v, p_v / lambda) = abar.  With d_v = log2(p_v / q_v),
+//   Z(2^x) = sum_{d_v > x} q_v + 2^-x sum_{d_v <= x} p_v
+// is non-increasing in x, so the crossing is bracketed by histogram passes: a pass sweeps the row,
+// adds q_v and p_v of the tokens inside the current bracket [lo, hi) to 64 bins (fixed point, so the
+// sums do not depend on the order of the atomics; 8 copies per bin keep same-address collisions
+// to eight lanes) and the mass outside it to two per-lane sums; the bin whose edges straddle abar is
+// the next bracket.  After BUDGET_PASSES passes the bracket is 128 / 64^3 = 4.9e-4 wide in log2
+// lambda and lambda = B / (abar - A) with A the q-mass above it and B the p-mass at or below it;
+// that closed form is exact up to the few tokens whose ratio lies inside the last bracket (their
+// mass times the bracket width, ~1e-8 of Z for a vocabulary of 1e5 tokens).
+// abar = 1 returns the smallest ratio (the largest lambda that still accepts everything).
+// =================================================================================================
+constexpr int BUDGET_BINS = 64, BUDGET_COPIES = 8, BUDGET_PASSES = 3;
+constexpr float BUDGET_RANGE = 64.f;                       // first bracket: ratios in [2^-64, 2^64)
+constexpr double BUDGET_FIX = 36028797018963968.0;         // 2^55: fixed-point unit of the bin sums
+
+// x in [0, 1] as an integer multiple of 2^-55, truncated: 31 bits from one conversion, 24 more from
+// the exact remainder (fp32 holds 24 significant bits, so nothing of x is lost above 2^-55).
+__device__ __forceinline__ unsigned long long to_fixed(float x)
+{
+    const uint32_t hi = (uint32_t)(x * 2147483648.0f);                          // floor(x 2^31)
+    const float rem = __builtin_fmaf(-(float)hi, 4.656612873077393e-10f, x);     // x - hi 2^-31, exact
+    const uint32_t lo = (uint32_t)(rem * 36028797018963968.0f);                  // floor(rem 2^55) < 2^24
+    return ((unsigned long long)hi << 24) + lo;
+}
+
+template <class ET>
+__global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
+{
+    constexpr int VEC = ET::VEC;
+    __shared__ unsigned long long hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
+    __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const float NaN = __uint_as_float(0x7fc00000u);
+    const uint8_t flag = A.rowflag[t];
+    const float abar_f = A.row_target ? A.row_target[t] : A.target;
+    if (flag != ROW_OK || !(abar_f > 0.f) || abar_f > 1.f) {
+        if (lane == 0) A.lambda_out[t] = flag == ROW_PADDING ? 0.f : NaN;
+        return;
+    }
+    const double abar = (double)abar_f;
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const int64_t V = A.V;
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
+    const float Aq = (float)(A.lse_q[t] * LOG2E_D);
+    const float Ap = (float)(A.lse_p[t] * LOG2E_D);
+    const int copy = lane & (BUDGET_COPIES - 1);
+
+    float lo = -BUDGET_RANGE, hi = BUDGET_RANGE;
+    double A_above = 0.0, B_below = 0.0;                    // wave-uniform: mass resolved outside the bracket
+    double lambda = 0.0;
+    bool done = false;
+    float dmin = __uint_as_float(0x7f800000u);
+    for (int pass = 0; pass < BUDGET_PASSES && !done; ++pass) {
+        for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0; hp[e] = 0; }
+        lds_sync();
+        const float inv_w = (float)BUDGET_BINS / (hi - lo);
+        double qa = 0.0, pb = 0.0;
+        auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+            float pbf = 0.f, qaf = 0.f;                     // this chunk's mass below / above the bracket
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
+                const float d = ap - aq;
+                const float q = __builtin_amdgcn_exp2f(aq), p = __builtin_amdgcn_exp2f(ap);
+                pbf += d < lo ? p : 0.f;                    // at or below every lambda of the bracket
+                qaf += d >= hi ? q : 0.f;                   // above every lambda of the bracket
+                if (d >= lo && d < hi) {                    // (both probabilities 0 give NaN: no mass)
+                    int b = (int)((d - lo) * inv_w);
+                    b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
+                    atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(q));
+                    atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(p));
+                }
+                if (pass == 0) dmin = (q > 0.f && p > 0.f) ? fminf(dmin, d) : dmin;
+            }
+            pb += (double)pbf;
+            qa += (double)qaf;
+        };
+        const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
+        if (nit > 0) {
+            constexpr int D = 3;                            // loads in flight per tensor and lane
+            const uint32_t last = nit - 1;
+            u32x4 wq[D], wp[D];
+#pragma unroll
+            for (int d2 = 0; d2 < D; ++d2) {
+                const uint32_t n = ((uint32_t)d2 < last ? (uint32_t)d2 : last) * WAVE + lane;
+                wq[d2] = stream_load(as_global_vec(rowq) + n);
+                wp[d2] = stream_load(as_global_vec(rowp) + n);
+            }
+            for (uint32_t it = 0; it < nit; it += D) {
+#pragma unroll
+                for (int d2 = 0; d2 < D; ++d2) {
+                    const u32x4 cq = wq[d2], cp = wp[d2];
+                    const uint32_t n = (it + D + d2 < last ? it + D + d2 : last) * WAVE + lane;
+                    wq[d2] = stream_load(as_global_vec(rowq) + n);
+                    wp[d2] = stream_load(as_global_vec(rowp) + n);
+                    if (d2 == 0 || it + d2 < nit) {
+                        float fq[VEC], fp[VEC];
+                        ET::unpack(cq, fq);
+                        ET::unpack(cp, fp);
+                        account(fq, fp);
+                    }
+                }
+            }
+        }
+        {
+            const uint32_t c = nit * WAVE + lane;
+            if (c < nchunks) {
+                float fq[VEC], fp[VEC];
+                load_chunk<ET>(rowq, c, nfull, tail, fq);
+                load_chunk<ET>(rowp, c, nfull, tail, fp);
+                account(fq, fp);
+            }
+        }
+        A_above = wave_sum(qa);
+        B_below = wave_sum(pb);
+        lds_sync();
+        // lane b owns bin b: its q- and p-mass, then the q-mass of the bins from b up and the p-mass below b
+        unsigned long long uq = 0, up = 0;
+#pragma unroll 4
+        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { uq += hq[lane * BUDGET_COPIES + c2]; up += hp[lane * BUDGET_COPIES + c2]; }
+        const double Qb = (double)uq / BUDGET_FIX, Pbin = (double)up / BUDGET_FIX;
+        sq_[lane] = Qb; sp_[lane] = Pbin;
+        lds_sync();
+        double Qsuf = 0.0, Ppre = 0.0, Ptot = 0.0;
+#pragma unroll 4
+        for (int j = 0; j < BUDGET_BINS; ++j) {
+            const double qj = sq_[j], pj = sp_[j];
+            Qsuf += j >= lane ? qj : 0.0;
+            Ppre += j < lane ? pj : 0.0;
+            Ptot += pj;
+        }
+        lds_sync();
+        const float w = (hi - lo) / (float)BUDGET_BINS;
+        const float edge = lo + w * (float)lane;            // lower edge of this lane's bin
+        const double Zedge = A_above + Qsuf + (B_below + Ppre) * (double)__builtin_amdgcn_exp2f(-edge);
+        const double Zhi = A_above + (B_below + Ptot) * (double)__builtin_amdgcn_exp2f(-hi);
+        const int n_true = __popcll(__ballot(Zedge >= abar));
+        // Z(lambda -> 0) is all the mass that can be kept at all.  A budget at (or within rounding of)
+        // it is met by every lambda up to the smallest ratio, which is the answer; Z is flat there,
+        // so the bracket search would be deciding on rounding noise.
+        const double Zmax = A_above + lane_value_d(Qsuf, 0);
+        if (pass == 0 && (n_true == 0 || abar >= Zmax * (1.0 - 1e-6))) {
+            lambda = (double)__builtin_amdgcn_exp2f(-uniform_f(wave_max(-dmin)));
+            done = true;
+        } else if (pass == 0 && Zhi >= abar) {
+            lambda = (B_below + Ptot) / (abar - A_above);   // beyond 2^64: every ratio is below lambda
+            done = true;
+        } else {
+            int bstar = n_true > 0 ? n_true - 1 : 0;
+            bstar = bstar < BUDGET_BINS - 1 ? bstar : BUDGET_BINS - 1;
+            // masses as seen by lane bstar, made wave-uniform
+            const double Qs = lane_value_d(Qsuf, bstar), Pp = lane_value_d(Ppre, bstar);
+            const double Qself = lane_value_d(Qb, bstar), Pself = lane_value_d(Pbin, bstar);
+            const float nlo = lo + w * (float)bstar;
+            if (pass == BUDGET_PASSES - 1) {
+                const double Aend = A_above + (Qs - Qself), Bend = B_below + Pp + Pself;
+                lambda = Bend / (abar - Aend);
+                const double l_lo = (double)__builtin_amdgcn_exp2f(nlo), l_hi = (double)__builtin_amdgcn_exp2f(nlo + w);
+                lambda = lambda < l_lo ? l_lo : (lambda > l_hi ? l_hi : lambda);
+                done = true;
+            }
+            lo = nlo;
+            hi = nlo + w;
+        }
+    }
+    if (lane == 0) A.lambda_out[t] = (float)lambda;
+}
+
+// =================================================================================================
 // Gradient of the distillation term KL(SG(p) || q) of Sec. 4.2 (3) with respect to the actor
 // logits: g_t[v] = w_t (q_t(v) - p_t(v)), q = 2^(lq log2e - LSEq log2e), p likewise.  A second
 // streaming pass: reads both logit rows once, writes one row.  A workgroup of 256 threads covers
@@ -1392,6 +1567,15 @@ hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st)
     const dim3 grid((unsigned)a.T), block(WAVE);
     if (dtype == JP_BF16) hipLaunchKernelGGL((token_logprob_kernel<Bf16Elem>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((token_logprob_kernel<F32Elem>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (dtype == JP_BF16) hipLaunchKernelGGL((budget_kernel<Bf16Elem>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((budget_kernel<F32Elem>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

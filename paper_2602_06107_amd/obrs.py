@@ -28,7 +28,7 @@ JP_F_TRUNCATE, JP_F_IDENTITY, JP_F_BAND = 0, 1, 2
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
            "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
            "jp_obrs_forward_stored", "jp_obrs_token_logprob", "jp_obrs_forward3",
-           "jp_obrs_forward3_workspace_bytes",
+           "jp_obrs_forward3_workspace_bytes", "jp_obrs_lambda_for_budget",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -97,6 +97,10 @@ _lib.jp_obrs_forward3.restype = C.c_int
 _lib.jp_obrs_forward3.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
                                   C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(Params),
                                   C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_lambda_for_budget.restype = C.c_int
+_lib.jp_obrs_lambda_for_budget.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                           C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                           C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -218,6 +222,20 @@ def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c
                               buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
+
+
+def jp_obrs_lambda_for_budget(actor, policy, target, buf: Buffers, row_target=None, out=None, stream=None):
+    """Per-row lambda whose OBRS rule accepts the fraction ``target`` (or ``row_target[t]``); needs the
+    log-sum-exps a preceding jp_obrs_rows / jp_obrs_forward call left in ``buf.workspace``."""
+    T, V, stride, dt = _logit_args(actor, policy)
+    if out is None:
+        out = torch.empty(T, dtype=torch.float32, device=actor.device)
+    st = _lib.jp_obrs_lambda_for_budget(_p(actor), _p(policy), T, V, stride, dt, _p(row_target), float(target),
+                                        _p(out), _p(buf.workspace), buf.workspace.numel(),
+                                        _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+    return out
 
 
 def jp_obrs_token_logprob(logits, sampled_ids, out=None, stream=None):
