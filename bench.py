@@ -25,9 +25,9 @@ HBM_PEAK_GBS = 8000.0
 # command (see profiles/), scaled by the counter reading of a plain copy of known size.
 # None until measured for the workload below.
 MEASURED_TRAFFIC_BYTES = {
-    # (T, V, k): FETCH_SIZE 2 546 150 KiB x 2.0 + WRITE_SIZE 6 474 KiB x 1.0
+    # (T, V, k): FETCH_SIZE 2 545 790 KiB x 2.0 + WRITE_SIZE 6 461 KiB x 1.0
     # (profiles/row_kernel_rollout_T8192_V151936_k64.md)
-    (8192, 151936, 64): int(2546150 * 1024 * 2.0 + 6474 * 1024 * 1.0),
+    (8192, 151936, 64): int(2545790 * 1024 * 2.0 + 6461 * 1024 * 1.0),
 }
 
 
