@@ -248,7 +248,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
             if (row < M) {
                 float *crow = C + (int64_t)row * G.ldc + tile_n * BN + wn * 128 + li;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) crow[j * 32] = acc[i][j][r];
+                for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(acc[i][j][r], crow + j * 32);
             }
         }
     }
