@@ -132,6 +132,20 @@ static double kept_mass(double logq_v, double logp_v, double lambda)
     return qv < pv ? qv : pv;
 }
 
+/* From log q(x) and log p(x) already in `out`: their difference, the acceptance probability and
+ * the Bernoulli draw (shared by the two-tensor and the stored-actor form of a row).             */
+static void accept_and_mask(jpo_row_out *out, double u, double lambda)
+{
+    out->logratio = out->logp_x - out->logq_x;
+
+    /* Eq. obrs_accept: a(x) = min(1, p(x) / (lambda q(x))) */
+    double r = exp(out->logratio) / lambda;
+    out->accept = r < 1.0 ? r : 1.0;
+
+    /* Mask(x) ~ Bernoulli(a(x)), realised as U(0,1) < a  (Alg. 2) */
+    out->mask = (u < out->accept) ? 1 : 0;
+}
+
 /* ---- one token position ------------------------------------------------
  * lq, lp: logits of the rollout and the target model over V tokens.
  * x: sampled token (x < 0 marks a padding row), u: uniform in [0,1).
@@ -148,17 +162,10 @@ void jpo_row(const double *lq, const double *lp, int64_t V, int32_t x, double u,
     out->lse_q = lse_q;
     out->lse_p = lse_p;
 
-    /* log-probabilities of the sampled token and their difference */
+    /* log-probabilities of the sampled token */
     out->logq_x = lq[x] - lse_q;
     out->logp_x = lp[x] - lse_p;
-    out->logratio = out->logp_x - out->logq_x;
-
-    /* Eq. obrs_accept: a(x) = min(1, p(x) / (lambda q(x))) */
-    double r = exp(out->logratio) / lambda;
-    out->accept = r < 1.0 ? r : 1.0;
-
-    /* Mask(x) ~ Bernoulli(a(x)), realised as U(0,1) < a  (Alg. 2) */
-    out->mask = (u < out->accept) ? 1 : 0;
+    accept_and_mask(out, u, lambda);
 
     /* V_k = top-k(q) U top-k(p), a set (Sec. 4.4.1) */
     int32_t *kq = (int32_t *)malloc((size_t)k * sizeof(int32_t));
@@ -232,10 +239,7 @@ void jpo_row_stored(const double *lp, int64_t V, const int32_t *ids_q, const dou
     out->lse_p = lse_p;
     out->logq_x = logq_x;
     out->logp_x = lp[x] - lse_p;
-    out->logratio = out->logp_x - out->logq_x;
-    double r = exp(out->logratio) / lambda;
-    out->accept = r < 1.0 ? r : 1.0;
-    out->mask = (u < out->accept) ? 1 : 0;
+    accept_and_mask(out, u, lambda);
 
     /* the stored list: first occurrence of every valid id */
     double *qlog = (double *)malloc((size_t)V * sizeof(double));
@@ -438,6 +442,30 @@ static int cmp_ratio(const void *a, const void *b)
     return (ra > rb) - (ra < rb);
 }
 
+/* Sort the n (ratio, q-mass, p-mass) entries and solve Z(lambda) = abar on the piece where Z crosses it. */
+static double solve_budget(jpo_ratio *e, int64_t n, double abar)
+{
+    if (n == 0) return NAN;
+    qsort(e, (size_t)n, sizeof(jpo_ratio), cmp_ratio);
+    /* A = mass of q on ratios above the piece, B = mass of p on ratios at or below it */
+    double A = 0.0, B = 0.0, lambda = NAN;
+    for (int64_t i = 0; i < n; ++i) A += e[i].q;
+    /* piece 0 is lambda <= r_(1): Z = A (all of q that can be kept); it holds the budget only if abar >= A */
+    if (abar >= A) { lambda = e[0].r; return lambda; }
+    for (int64_t i = 0; i < n; ++i) {
+        A -= e[i].q;
+        B += e[i].p;
+        /* piece i+1: r_(i+1) <= lambda < r_(i+2) (the last piece is unbounded above) */
+        double upper = (i + 1 < n) ? e[i + 1].r : INFINITY;
+        double z_upper = (i + 1 < n) ? A + B / upper : 0.0;
+        if (abar > z_upper || i + 1 == n) {
+            lambda = B / (abar - A);
+            break;
+        }
+    }
+    return lambda;
+}
+
 double jpo_lambda_for_budget(const double *lq, const double *lp, int64_t V, double abar)
 {
     if (!(abar > 0.0) || abar > 1.0) return NAN;
@@ -452,24 +480,7 @@ double jpo_lambda_for_budget(const double *lq, const double *lp, int64_t V, doub
         e[n].p = p;
         ++n;
     }
-    qsort(e, (size_t)n, sizeof(jpo_ratio), cmp_ratio);
-    /* A = mass of q on ratios above the piece, B = mass of p on ratios at or below it */
-    double A = 0.0, B = 0.0, lambda = NAN;
-    for (int64_t i = 0; i < n; ++i) A += e[i].q;
-    if (n == 0) { free(e); return NAN; }
-    /* piece 0 is lambda <= r_(1): Z = A (all of q that can be kept); it holds the budget only if abar >= A */
-    if (abar >= A) { lambda = e[0].r; free(e); return lambda; }
-    for (int64_t i = 0; i < n; ++i) {
-        A -= e[i].q;
-        B += e[i].p;
-        /* piece i+1: r_(i+1) <= lambda < r_(i+2) (the last piece is unbounded above) */
-        double upper = (i + 1 < n) ? e[i + 1].r : INFINITY;
-        double z_upper = (i + 1 < n) ? A + B / upper : 0.0;
-        if (abar > z_upper || i + 1 == n) {
-            lambda = B / (abar - A);
-            break;
-        }
-    }
+    double lambda = solve_budget(e, n, abar);
     free(e);
     return lambda;
 }
@@ -489,6 +500,44 @@ void jpo_lambda_for_budget_rows(const void *actor, const void *policy, int dtype
     }
     free(lp);
     free(lq);
+}
+
+/* One lambda for a whole batch: (1/n) sum_t Z_t(lambda) = abar over the n valid rows.  The mean
+ * of the rows' Z functions has the same shape as one of them (sum of the q-masses above lambda
+ * plus 1/lambda times the p-masses at or below it, every row weighted 1/n), so the same
+ * sort-and-solve applies to the pooled ratios.  Padding rows (x < 0) are left out.  Returns NaN for
+ * abar outside (0, 1] or an empty batch.                                                       */
+double jpo_lambda_for_budget_batch(const void *actor, const void *policy, int dtype, int64_t T,
+                                   int64_t V, int64_t row_stride, const int32_t *x, double abar)
+{
+    if (!(abar > 0.0) || abar > 1.0) return NAN;
+    size_t esz = dtype == JPO_F32 ? 4 : dtype == JPO_BF16 ? 2 : 8;
+    int64_t n_rows = 0;
+    for (int64_t t = 0; t < T; ++t) n_rows += x[t] >= 0 ? 1 : 0;
+    if (n_rows == 0) return NAN;
+    double *lq = (double *)malloc((size_t)V * sizeof(double));
+    double *lp = (double *)malloc((size_t)V * sizeof(double));
+    jpo_ratio *e = (jpo_ratio *)malloc((size_t)n_rows * (size_t)V * sizeof(jpo_ratio));
+    int64_t n = 0;
+    for (int64_t t = 0; t < T; ++t) {
+        if (x[t] < 0) continue;
+        jpo_widen_row((const char *)actor + (size_t)t * (size_t)row_stride * esz, dtype, V, lq);
+        jpo_widen_row((const char *)policy + (size_t)t * (size_t)row_stride * esz, dtype, V, lp);
+        double lse_q = jpo_logsumexp(lq, V), lse_p = jpo_logsumexp(lp, V);
+        for (int64_t v = 0; v < V; ++v) {
+            double q = exp(lq[v] - lse_q), p = exp(lp[v] - lse_p);
+            if (!(q > 0.0) || !(p > 0.0)) continue;
+            e[n].r = exp((lp[v] - lse_p) - (lq[v] - lse_q));
+            e[n].q = q / (double)n_rows;
+            e[n].p = p / (double)n_rows;
+            ++n;
+        }
+    }
+    free(lp);
+    free(lq);
+    double lambda = solve_budget(e, n, abar);
+    free(e);
+    return lambda;
 }
 
 /* The adjustment function F of the importance weight (Sec. 2, related work; Eq. obrs_ppo applies it

@@ -112,6 +112,9 @@ def lib():
         l.jpo_lambda_for_budget_rows.restype = None
         l.jpo_lambda_for_budget_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64,
                                                  C.c_int64, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p]
+        l.jpo_lambda_for_budget_batch.restype = C.c_double
+        l.jpo_lambda_for_budget_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64,
+                                                  C.c_int64, C.c_void_p, C.c_double]
         l.jpo_max_threads.restype = C.c_int
         l.jpo_widen_row.restype = None
         l.jpo_widen_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
@@ -228,6 +231,16 @@ def lambda_for_budget_rows(actor: np.ndarray, policy: np.ndarray, x, target: flo
     lib().jpo_lambda_for_budget_rows(_ptr(a), _ptr(policy), code, T, V, a.strides[0] // a.itemsize,
                                      _ptr(x), _ptr(rt), float(target), _ptr(out))
     return out
+
+
+def lambda_for_budget_batch(actor: np.ndarray, policy: np.ndarray, x, target: float) -> float:
+    """One lambda with mean_t Z_t(lambda) = target over the valid rows of the batch."""
+    assert actor.shape == policy.shape and actor.ndim == 2 and actor.dtype == policy.dtype
+    a, code = storage_view(actor)
+    T, V = a.shape
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    return lib().jpo_lambda_for_budget_batch(_ptr(a), _ptr(policy), code, T, V, a.strides[0] // a.itemsize,
+                                             _ptr(x), float(target))
 
 
 F_TRUNCATE, F_IDENTITY, F_BAND = 0, 1, 2

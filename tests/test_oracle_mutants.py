@@ -62,7 +62,11 @@ MUTANTS = [
     ("budget solver: keeps the mass of q at or below the piece in A",
      "A -= e[i].q;\n        B += e[i].p;", "B += e[i].p;"),
     ("budget solver: budget 1 returns the largest ratio",
-     "if (abar >= A) { lambda = e[0].r; free(e); return lambda; }", "if (abar >= A) { lambda = e[n - 1].r; free(e); return lambda; }"),
+     "if (abar >= A) { lambda = e[0].r; return lambda; }", "if (abar >= A) { lambda = e[n - 1].r; return lambda; }"),
+    ("batch budget solver: rows are not weighted by 1/n",
+     "e[n].q = q / (double)n_rows;\n            e[n].p = p / (double)n_rows;", "e[n].q = q;\n            e[n].p = p;"),
+    ("batch budget solver: the mean runs over padding rows too",
+     "for (int64_t t = 0; t < T; ++t) n_rows += x[t] >= 0 ? 1 : 0;", "for (int64_t t = 0; t < T; ++t) n_rows += 1;"),
     ("distillation gradient has the wrong sign",
      "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
     ("distillation gradient drops the row weight",

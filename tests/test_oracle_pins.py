@@ -706,3 +706,35 @@ def test_lambda_for_budget_rows_driver():
             continue
         assert got[t] == orc.lambda_for_budget(a[t], p[t], float(rt[t]))
         assert _z_of_lambda(_softmax64(a[t]), _softmax64(p[t]), got_scalar[t]) == pytest.approx(0.5, rel=1e-12)
+
+
+def test_lambda_for_budget_batch_against_bisection_on_the_mean():
+    rng = np.random.default_rng(557)
+    T, V = 9, 64
+    a = rng.normal(0, 2, (T, V)).astype(np.float32)
+    p = (a + rng.normal(0, 1, (T, V)) * rng.uniform(0.1, 2.0, (T, 1))).astype(np.float32)
+    x = np.array([1, 2, -1, 3, 4, 5, -1, 6, 7], dtype=np.int32)
+    valid = x >= 0
+    Q = scipy.special.softmax(a[valid].astype(np.float64), axis=1)
+    P = scipy.special.softmax(p[valid].astype(np.float64), axis=1)
+
+    def zbar(lam):
+        return float(np.minimum(Q, P / lam).sum(axis=1).mean())
+
+    prev = None
+    for abar in (0.95, 0.6, 0.3, 0.02):
+        lam = orc.lambda_for_budget_batch(a, p, x, abar)
+        assert zbar(lam) == pytest.approx(abar, rel=1e-12)
+        lo, hi = 1e-12, 1e12
+        for _ in range(200):
+            mid = math.sqrt(lo * hi)
+            lo, hi = (mid, hi) if zbar(mid) > abar else (lo, mid)
+        assert lam == pytest.approx(math.sqrt(lo * hi), rel=1e-9)
+        assert prev is None or lam > prev
+        prev = lam
+    assert orc.lambda_for_budget_batch(a, p, x, 1.0) == pytest.approx(float((P / Q).min()), rel=1e-12)
+    # one valid row: the per-row solver's answer
+    x1 = np.full(T, -1, np.int32); x1[4] = 0
+    assert orc.lambda_for_budget_batch(a, p, x1, 0.4) == pytest.approx(orc.lambda_for_budget(a[4], p[4], 0.4), rel=1e-13)
+    assert math.isnan(orc.lambda_for_budget_batch(a, p, np.full(T, -1, np.int32), 0.5))
+    assert math.isnan(orc.lambda_for_budget_batch(a, p, x, 0.0))
