@@ -259,6 +259,22 @@ jp_status jp_obrs_lambda_for_budget(const void *actor_logits, const void *policy
                                     const void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One scaling factor for a whole batch: the lambda with (1/n) sum_t Z_t(lambda) = target over the n
+ * valid rows (the mean acceptance of the batch under one global lambda, which is how Sec. 4 uses
+ * lambda).  Same search as jp_obrs_lambda_for_budget with the histogram bins summed over the rows
+ * in device memory; three sweeps of the two tensors, nothing passes through the host.
+ *   out_lambda: device, one fp32 (NaN if the batch has no valid row)
+ *   scratch:    device, jp_obrs_budget_scratch_bytes() bytes, 16-byte aligned, contents irrelevant
+ * workspace as for jp_obrs_lambda_for_budget.
+ */
+size_t jp_obrs_budget_scratch_bytes(void);
+jp_status jp_obrs_lambda_for_budget_batch(const void *actor_logits, const void *policy_logits,
+                                          int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                                          float target, float *out_lambda,
+                                          const void *workspace, size_t workspace_bytes,
+                                          void *scratch, size_t scratch_bytes, void *stream);
+
+/*
  * Gradient of the on-policy distillation term of Sec. 4.2 (3), Eq. distill_loss, with respect to
  * the actor logits.  The term per token is KL(SG(p_t) || q_t) with the target p_t held fixed and
  * q_t = softmax(actor logits), so d/d lq_t[v] = q_t(v) - p_t(v).  This call writes

@@ -415,6 +415,33 @@ jp_status jp_obrs_lambda_for_budget(const void *actor_logits, const void *policy
     return JP_OK;
 }
 
+size_t jp_obrs_budget_scratch_bytes(void) { return round_up(sizeof(jp::BudgetBatchState)); }
+
+/* One scaling factor for the whole batch: mean_t Z_t(lambda) = target. */
+jp_status jp_obrs_lambda_for_budget_batch(const void *actor_logits, const void *policy_logits, int64_t T,
+                                          int64_t V, int64_t row_stride, jp_dtype dt, float target,
+                                          float *out_lambda, const void *workspace, size_t workspace_bytes,
+                                          void *scratch, size_t scratch_bytes, void *stream)
+{
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s != JP_OK) return s;
+    if (!(target > 0.f) || target > 1.f) return JP_ERR_PARAM;
+    if (!out_lambda || (T > 0 && (!actor_logits || !policy_logits))) return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(actor_logits) || !aligned16(policy_logits) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    const Workspace w = carve(const_cast<void *>(workspace), T);
+    if (!workspace || workspace_bytes < w.bytes) return JP_ERR_WORKSPACE;
+    if (!scratch || scratch_bytes < jp_obrs_budget_scratch_bytes()) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0 || ((uintptr_t)scratch & 15u) != 0) return JP_ERR_ALIGN;
+    jp::BudgetArgs b{};
+    b.actor = actor_logits; b.policy = policy_logits; b.T = T; b.V = V; b.stride = row_stride;
+    b.lse_q = w.lse_q; b.lse_p = w.lse_p; b.rowflag = w.rowflag;
+    b.row_target = nullptr; b.target = target; b.lambda_out = nullptr;
+    if (jp::launch_budget_batch(b, (int)dt, (jp::BudgetBatchState *)scratch, out_lambda, (hipStream_t)stream) != hipSuccess)
+        return JP_ERR_HIP;
+    return JP_OK;
+}
+
 /* Gradient of the distillation term with respect to the actor logits (second streaming pass). */
 jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
                                int64_t row_stride, jp_dtype dt, const float *row_scale, float scale,
@@ -458,6 +485,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 6; }
+int jp_obrs_abi_version(void) { return 7; }
 
 }  // extern "C"

@@ -107,7 +107,17 @@ struct BudgetArgs {
     float *lambda_out;                // [T]
 };
 
+// Device-resident state of the per-batch budget search (in the caller's scratch buffer).
+struct BudgetBatchState {
+    float lo, hi;                     // current bracket, log2 of the ratio
+    int done, dmin_ord;               // finished flag; smallest log2 ratio as an order-preserving int
+    double lambda;
+    unsigned long long n_rows, above, below;   // valid rows; mass outside the bracket (2^-32 units)
+    unsigned long long bq[64], bp[64];         // bin sums over all rows (2^-32 units)
+};
+
 hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st);
+hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState *S, float *out_lambda, hipStream_t st);
 hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st);   // a.actor unused

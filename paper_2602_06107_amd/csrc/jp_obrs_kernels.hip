@@ -1100,10 +1100,144 @@ __device__ __forceinline__ unsigned long long to_fixed(float x)
     return ((unsigned long long)hi << 24) + lo;
 }
 
+// One histogram sweep of a row pair for the bracket [lo, hi): q- and p-mass of the tokens inside it
+// go to the LDS bins hq / hp (2^-55 units), the mass outside it to the per-lane sums qa (above) and
+// pb (below); the first pass also tracks the smallest log2 ratio.
+template <class ET>
+__device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
+                                             float lo, float hi, bool first_pass, unsigned long long *hq,
+                                             unsigned long long *hp, double &qa, double &pb, float &dmin)
+{
+    constexpr int VEC = ET::VEC;
+    const int lane = threadIdx.x;
+    const uint32_t nfull = (uint32_t)(V / VEC);
+    const int tail = (int)(V - (int64_t)nfull * VEC);
+    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
+    const int copy = lane & (BUDGET_COPIES - 1);
+    for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0; hp[e] = 0; }
+    lds_sync();
+    const float inv_w = (float)BUDGET_BINS / (hi - lo);
+    qa = 0.0;
+    pb = 0.0;
+    auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+        float pbf = 0.f, qaf = 0.f;                     // this chunk's mass below / above the bracket
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
+            const float d = ap - aq;
+            const float q = __builtin_amdgcn_exp2f(aq), p = __builtin_amdgcn_exp2f(ap);
+            pbf += d < lo ? p : 0.f;                    // at or below every lambda of the bracket
+            qaf += d >= hi ? q : 0.f;                   // above every lambda of the bracket
+            if (d >= lo && d < hi) {                    // (both probabilities 0 give NaN: no mass)
+                int b = (int)((d - lo) * inv_w);
+                b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
+                atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(q));
+                atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(p));
+            }
+            if (first_pass) dmin = (q > 0.f && p > 0.f) ? fminf(dmin, d) : dmin;
+        }
+        pb += (double)pbf;
+        qa += (double)qaf;
+    };
+    const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
+    if (nit > 0) {
+        constexpr int D = 3;                            // loads in flight per tensor and lane
+        const uint32_t last = nit - 1;
+        u32x4 wq[D], wp[D];
+#pragma unroll
+        for (int d2 = 0; d2 < D; ++d2) {
+            const uint32_t n = ((uint32_t)d2 < last ? (uint32_t)d2 : last) * WAVE + lane;
+            wq[d2] = stream_load(as_global_vec(rowq) + n);
+            wp[d2] = stream_load(as_global_vec(rowp) + n);
+        }
+        for (uint32_t it = 0; it < nit; it += D) {
+#pragma unroll
+            for (int d2 = 0; d2 < D; ++d2) {
+                const u32x4 cq = wq[d2], cp = wp[d2];
+                const uint32_t n = (it + D + d2 < last ? it + D + d2 : last) * WAVE + lane;
+                wq[d2] = stream_load(as_global_vec(rowq) + n);
+                wp[d2] = stream_load(as_global_vec(rowp) + n);
+                if (d2 == 0 || it + d2 < nit) {
+                    float fq[VEC], fp[VEC];
+                    ET::unpack(cq, fq);
+                    ET::unpack(cp, fp);
+                    account(fq, fp);
+                }
+            }
+        }
+    }
+    {
+        const uint32_t c = nit * WAVE + lane;
+        if (c < nchunks) {
+            float fq[VEC], fp[VEC];
+            load_chunk<ET>(rowq, c, nfull, tail, fq);
+            load_chunk<ET>(rowp, c, nfull, tail, fp);
+            account(fq, fp);
+        }
+    }
+    lds_sync();
+}
+
+// One step of the bracket search, run by a whole wave: lane b brings the q- and p-mass of bin b
+// (Qb, Pbin); A_above / B_below are the masses outside the bracket, `goal` the value Z must reach
+// (abar, or abar times the number of rows when the masses are sums over a batch); dmin the
+// smallest log2 ratio seen.  Narrows [lo, hi) to the bin that straddles the goal, or finishes
+// (returns true) with lambda.  sq_ / sp_: BUDGET_BINS doubles of LDS each.
+__device__ __forceinline__ bool budget_step(double goal, double A_above, double B_below, double Qb, double Pbin,
+                                            float &lo, float &hi, int pass, float dmin, double *sq_, double *sp_,
+                                            double &lambda)
+{
+    const int lane = threadIdx.x;
+    sq_[lane] = Qb; sp_[lane] = Pbin;
+    lds_sync();
+    // the q-mass of the bins from this lane's up, the p-mass of the bins below it
+    double Qsuf = 0.0, Ppre = 0.0, Ptot = 0.0;
+#pragma unroll 4
+    for (int j = 0; j < BUDGET_BINS; ++j) {
+        const double qj = sq_[j], pj = sp_[j];
+        Qsuf += j >= lane ? qj : 0.0;
+        Ppre += j < lane ? pj : 0.0;
+        Ptot += pj;
+    }
+    lds_sync();
+    const float w = (hi - lo) / (float)BUDGET_BINS;
+    const float edge = lo + w * (float)lane;            // lower edge of this lane's bin
+    const double Zedge = A_above + Qsuf + (B_below + Ppre) * (double)__builtin_amdgcn_exp2f(-edge);
+    const double Zhi = A_above + (B_below + Ptot) * (double)__builtin_amdgcn_exp2f(-hi);
+    const int n_true = __popcll(__ballot(Zedge >= goal));
+    // Z(lambda -> 0) is all the mass that can be kept at all.  A budget at (or within rounding of)
+    // it is met by every lambda up to the smallest ratio, which is the answer; Z is flat there,
+    // so the bracket search would be deciding on rounding noise.
+    const double Zmax = A_above + lane_value_d(Qsuf, 0);
+    if (pass == 0 && (n_true == 0 || goal >= Zmax * (1.0 - 1e-6))) {
+        lambda = (double)__builtin_amdgcn_exp2f(dmin);
+        return true;
+    }
+    if (pass == 0 && Zhi >= goal) {
+        lambda = (B_below + Ptot) / (goal - A_above);   // beyond 2^64: every ratio is below lambda
+        return true;
+    }
+    int bstar = n_true > 0 ? n_true - 1 : 0;
+    bstar = bstar < BUDGET_BINS - 1 ? bstar : BUDGET_BINS - 1;
+    // masses as seen by lane bstar, made wave-uniform
+    const double Qs = lane_value_d(Qsuf, bstar), Pp = lane_value_d(Ppre, bstar);
+    const double Qself = lane_value_d(Qb, bstar), Pself = lane_value_d(Pbin, bstar);
+    const float nlo = lo + w * (float)bstar;
+    lo = nlo;
+    hi = nlo + w;
+    if (pass == BUDGET_PASSES - 1) {
+        const double Aend = A_above + (Qs - Qself), Bend = B_below + Pp + Pself;
+        lambda = Bend / (goal - Aend);
+        const double l_lo = (double)__builtin_amdgcn_exp2f(nlo), l_hi = (double)__builtin_amdgcn_exp2f(nlo + w);
+        lambda = lambda < l_lo ? l_lo : (lambda > l_hi ? l_hi : lambda);
+        return true;
+    }
+    return false;
+}
+
 template <class ET>
 __global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
 {
-    constexpr int VEC = ET::VEC;
     __shared__ unsigned long long hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
     __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
     const int lane = threadIdx.x;
@@ -1115,136 +1249,108 @@ __global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
         if (lane == 0) A.lambda_out[t] = flag == ROW_PADDING ? 0.f : NaN;
         return;
     }
-    const double abar = (double)abar_f;
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
-    const int64_t V = A.V;
-    const uint32_t nfull = (uint32_t)(V / VEC);
-    const int tail = (int)(V - (int64_t)nfull * VEC);
-    const uint32_t nchunks = nfull + (tail ? 1u : 0u);
     const float Aq = (float)(A.lse_q[t] * LOG2E_D);
     const float Ap = (float)(A.lse_p[t] * LOG2E_D);
-    const int copy = lane & (BUDGET_COPIES - 1);
-
     float lo = -BUDGET_RANGE, hi = BUDGET_RANGE;
-    double A_above = 0.0, B_below = 0.0;                    // wave-uniform: mass resolved outside the bracket
     double lambda = 0.0;
-    bool done = false;
     float dmin = __uint_as_float(0x7f800000u);
-    for (int pass = 0; pass < BUDGET_PASSES && !done; ++pass) {
-        for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0; hp[e] = 0; }
-        lds_sync();
-        const float inv_w = (float)BUDGET_BINS / (hi - lo);
-        double qa = 0.0, pb = 0.0;
-        auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
-            float pbf = 0.f, qaf = 0.f;                     // this chunk's mass below / above the bracket
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
-                const float d = ap - aq;
-                const float q = __builtin_amdgcn_exp2f(aq), p = __builtin_amdgcn_exp2f(ap);
-                pbf += d < lo ? p : 0.f;                    // at or below every lambda of the bracket
-                qaf += d >= hi ? q : 0.f;                   // above every lambda of the bracket
-                if (d >= lo && d < hi) {                    // (both probabilities 0 give NaN: no mass)
-                    int b = (int)((d - lo) * inv_w);
-                    b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
-                    atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(q));
-                    atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(p));
-                }
-                if (pass == 0) dmin = (q > 0.f && p > 0.f) ? fminf(dmin, d) : dmin;
-            }
-            pb += (double)pbf;
-            qa += (double)qaf;
-        };
-        const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
-        if (nit > 0) {
-            constexpr int D = 3;                            // loads in flight per tensor and lane
-            const uint32_t last = nit - 1;
-            u32x4 wq[D], wp[D];
-#pragma unroll
-            for (int d2 = 0; d2 < D; ++d2) {
-                const uint32_t n = ((uint32_t)d2 < last ? (uint32_t)d2 : last) * WAVE + lane;
-                wq[d2] = stream_load(as_global_vec(rowq) + n);
-                wp[d2] = stream_load(as_global_vec(rowp) + n);
-            }
-            for (uint32_t it = 0; it < nit; it += D) {
-#pragma unroll
-                for (int d2 = 0; d2 < D; ++d2) {
-                    const u32x4 cq = wq[d2], cp = wp[d2];
-                    const uint32_t n = (it + D + d2 < last ? it + D + d2 : last) * WAVE + lane;
-                    wq[d2] = stream_load(as_global_vec(rowq) + n);
-                    wp[d2] = stream_load(as_global_vec(rowp) + n);
-                    if (d2 == 0 || it + d2 < nit) {
-                        float fq[VEC], fp[VEC];
-                        ET::unpack(cq, fq);
-                        ET::unpack(cp, fp);
-                        account(fq, fp);
-                    }
-                }
-            }
-        }
-        {
-            const uint32_t c = nit * WAVE + lane;
-            if (c < nchunks) {
-                float fq[VEC], fp[VEC];
-                load_chunk<ET>(rowq, c, nfull, tail, fq);
-                load_chunk<ET>(rowp, c, nfull, tail, fp);
-                account(fq, fp);
-            }
-        }
-        A_above = wave_sum(qa);
-        B_below = wave_sum(pb);
-        lds_sync();
-        // lane b owns bin b: its q- and p-mass, then the q-mass of the bins from b up and the p-mass below b
+    for (int pass = 0; pass < BUDGET_PASSES; ++pass) {
+        double qa, pb;
+        budget_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, pass == 0, hq, hp, qa, pb, dmin);
+        const double A_above = wave_sum(qa), B_below = wave_sum(pb);
+        // lane b owns bin b
         unsigned long long uq = 0, up = 0;
 #pragma unroll 4
         for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { uq += hq[lane * BUDGET_COPIES + c2]; up += hp[lane * BUDGET_COPIES + c2]; }
-        const double Qb = (double)uq / BUDGET_FIX, Pbin = (double)up / BUDGET_FIX;
-        sq_[lane] = Qb; sp_[lane] = Pbin;
-        lds_sync();
-        double Qsuf = 0.0, Ppre = 0.0, Ptot = 0.0;
-#pragma unroll 4
-        for (int j = 0; j < BUDGET_BINS; ++j) {
-            const double qj = sq_[j], pj = sp_[j];
-            Qsuf += j >= lane ? qj : 0.0;
-            Ppre += j < lane ? pj : 0.0;
-            Ptot += pj;
-        }
-        lds_sync();
-        const float w = (hi - lo) / (float)BUDGET_BINS;
-        const float edge = lo + w * (float)lane;            // lower edge of this lane's bin
-        const double Zedge = A_above + Qsuf + (B_below + Ppre) * (double)__builtin_amdgcn_exp2f(-edge);
-        const double Zhi = A_above + (B_below + Ptot) * (double)__builtin_amdgcn_exp2f(-hi);
-        const int n_true = __popcll(__ballot(Zedge >= abar));
-        // Z(lambda -> 0) is all the mass that can be kept at all.  A budget at (or within rounding of)
-        // it is met by every lambda up to the smallest ratio, which is the answer; Z is flat there,
-        // so the bracket search would be deciding on rounding noise.
-        const double Zmax = A_above + lane_value_d(Qsuf, 0);
-        if (pass == 0 && (n_true == 0 || abar >= Zmax * (1.0 - 1e-6))) {
-            lambda = (double)__builtin_amdgcn_exp2f(-uniform_f(wave_max(-dmin)));
-            done = true;
-        } else if (pass == 0 && Zhi >= abar) {
-            lambda = (B_below + Ptot) / (abar - A_above);   // beyond 2^64: every ratio is below lambda
-            done = true;
-        } else {
-            int bstar = n_true > 0 ? n_true - 1 : 0;
-            bstar = bstar < BUDGET_BINS - 1 ? bstar : BUDGET_BINS - 1;
-            // masses as seen by lane bstar, made wave-uniform
-            const double Qs = lane_value_d(Qsuf, bstar), Pp = lane_value_d(Ppre, bstar);
-            const double Qself = lane_value_d(Qb, bstar), Pself = lane_value_d(Pbin, bstar);
-            const float nlo = lo + w * (float)bstar;
-            if (pass == BUDGET_PASSES - 1) {
-                const double Aend = A_above + (Qs - Qself), Bend = B_below + Pp + Pself;
-                lambda = Bend / (abar - Aend);
-                const double l_lo = (double)__builtin_amdgcn_exp2f(nlo), l_hi = (double)__builtin_amdgcn_exp2f(nlo + w);
-                lambda = lambda < l_lo ? l_lo : (lambda > l_hi ? l_hi : lambda);
-                done = true;
-            }
-            lo = nlo;
-            hi = nlo + w;
-        }
+        const float dmin_w = pass == 0 ? -uniform_f(wave_max(-dmin)) : 0.f;
+        if (budget_step((double)abar_f, A_above, B_below, (double)uq / BUDGET_FIX, (double)up / BUDGET_FIX, lo, hi,
+                        pass, dmin_w, sq_, sp_, lambda))
+            break;
     }
     if (lane == 0) A.lambda_out[t] = (float)lambda;
+}
+
+// The same search for one lambda of a whole batch, mean_t Z_t(lambda) = abar: the bins of all rows are
+// summed in device memory (64-bit fixed point, 2^-32 units, so the sums are order-independent), a
+// one-wave kernel narrows the bracket between the sweeps, and nothing goes through the host.
+__global__ void budget_batch_init_kernel(BudgetBatchState *S)
+{
+    const int lane = threadIdx.x;
+    S->bq[lane] = 0; S->bp[lane] = 0;
+    if (lane == 0) {
+        S->lo = -BUDGET_RANGE; S->hi = BUDGET_RANGE; S->done = 0; S->lambda = 0.0;
+        S->n_rows = 0; S->above = 0; S->below = 0; S->dmin_ord = 0x7fffffff;
+    }
+}
+
+// float <-> int with the same order (for an atomic minimum over floats)
+__device__ __forceinline__ int float_order_int(float f)
+{
+    const int i = __float_as_int(f);
+    return i ^ ((i >> 31) & 0x7fffffff);
+}
+
+template <class ET>
+__global__ __launch_bounds__(64, 4) void budget_batch_pass_kernel(BudgetArgs A, BudgetBatchState *S, int pass)
+{
+    __shared__ unsigned long long hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    if (S->done || A.rowflag[t] != ROW_OK) return;
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const float Aq = (float)(A.lse_q[t] * LOG2E_D);
+    const float Ap = (float)(A.lse_p[t] * LOG2E_D);
+    const float lo = S->lo, hi = S->hi;
+    float dmin = __uint_as_float(0x7f800000u);
+    double qa, pb;
+    budget_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, pass == 0, hq, hp, qa, pb, dmin);
+    const double A_above = wave_sum(qa), B_below = wave_sum(pb);
+    unsigned long long uq = 0, up = 0;
+#pragma unroll 4
+    for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { uq += hq[lane * BUDGET_COPIES + c2]; up += hp[lane * BUDGET_COPIES + c2]; }
+    if (uq >> 23) atomicAdd(&S->bq[lane], uq >> 23);        // 2^-55 -> 2^-32 units
+    if (up >> 23) atomicAdd(&S->bp[lane], up >> 23);
+    if (pass == 0) dmin = -uniform_f(wave_max(-dmin));
+    if (lane == 0) {
+        atomicAdd(&S->above, (unsigned long long)(A_above * 4294967296.0));
+        atomicAdd(&S->below, (unsigned long long)(B_below * 4294967296.0));
+        if (pass == 0) {
+            atomicAdd(&S->n_rows, 1ull);
+            atomicMin(&S->dmin_ord, float_order_int(dmin));
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void budget_batch_scan_kernel(BudgetBatchState *S, float target, int pass, float *out_lambda)
+{
+    __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
+    const int lane = threadIdx.x;
+    if (S->done) return;
+    const double unit = 1.0 / 4294967296.0;
+    const unsigned long long n = S->n_rows;
+    const double Qb = (double)S->bq[lane] * unit, Pbin = (double)S->bp[lane] * unit;
+    const double A_above = (double)S->above * unit, B_below = (double)S->below * unit;
+    float lo = S->lo, hi = S->hi;
+    const int o = S->dmin_ord;
+    const float dmin = __int_as_float(o ^ ((o >> 31) & 0x7fffffff));
+    double lambda = 0.0;
+    bool done;
+    if (n == 0) {                                           // no valid row
+        lambda = __longlong_as_double(0x7ff8000000000000LL);
+        done = true;
+    } else {
+        done = budget_step((double)target * (double)n, A_above, B_below, Qb, Pbin, lo, hi, pass, dmin, sq_, sp_, lambda);
+    }
+    lds_sync();
+    S->bq[lane] = 0; S->bp[lane] = 0;                       // the next sweep starts from empty bins
+    if (lane == 0) {
+        S->above = 0; S->below = 0;
+        S->lo = lo; S->hi = hi;
+        if (done) { S->done = 1; S->lambda = lambda; *out_lambda = (float)lambda; }
+    }
 }
 
 // =================================================================================================
@@ -1576,6 +1682,20 @@ hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st)
     const dim3 grid((unsigned)a.T), block(WAVE);
     if (dtype == JP_BF16) hipLaunchKernelGGL((budget_kernel<Bf16Elem>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((budget_kernel<F32Elem>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState *S, float *out_lambda, hipStream_t st)
+{
+    hipLaunchKernelGGL(budget_batch_init_kernel, dim3(1), dim3(WAVE), 0, st, S);
+    for (int pass = 0; pass < BUDGET_PASSES; ++pass) {
+        if (a.T > 0) {
+            const dim3 grid((unsigned)a.T), block(WAVE);
+            if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_pass_kernel<Bf16Elem>), grid, block, 0, st, a, S, pass);
+            else hipLaunchKernelGGL((budget_batch_pass_kernel<F32Elem>), grid, block, 0, st, a, S, pass);
+        }
+        hipLaunchKernelGGL(budget_batch_scan_kernel, dim3(1), dim3(WAVE), 0, st, S, a.target, pass, out_lambda);
+    }
     return hipGetLastError();
 }
 

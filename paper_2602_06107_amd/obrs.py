@@ -29,6 +29,7 @@ EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obr
            "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
            "jp_obrs_forward_stored", "jp_obrs_token_logprob", "jp_obrs_forward3",
            "jp_obrs_forward3_workspace_bytes", "jp_obrs_lambda_for_budget",
+           "jp_obrs_lambda_for_budget_batch", "jp_obrs_budget_scratch_bytes",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -101,6 +102,12 @@ _lib.jp_obrs_lambda_for_budget.restype = C.c_int
 _lib.jp_obrs_lambda_for_budget.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                                            C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
                                            C.c_void_p]
+_lib.jp_obrs_budget_scratch_bytes.restype = C.c_size_t
+_lib.jp_obrs_budget_scratch_bytes.argtypes = []
+_lib.jp_obrs_lambda_for_budget_batch.restype = C.c_int
+_lib.jp_obrs_lambda_for_budget_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                                 C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                                 C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -233,6 +240,21 @@ def jp_obrs_lambda_for_budget(actor, policy, target, buf: Buffers, row_target=No
     st = _lib.jp_obrs_lambda_for_budget(_p(actor), _p(policy), T, V, stride, dt, _p(row_target), float(target),
                                         _p(out), _p(buf.workspace), buf.workspace.numel(),
                                         _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+    return out
+
+
+def jp_obrs_lambda_for_budget_batch(actor, policy, target, buf: Buffers, out=None, scratch=None, stream=None):
+    """One lambda with mean_t Z_t(lambda) = ``target`` over the batch -> device float32 [1]."""
+    T, V, stride, dt = _logit_args(actor, policy)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=actor.device)
+    if scratch is None:
+        scratch = torch.empty(_lib.jp_obrs_budget_scratch_bytes(), dtype=torch.uint8, device=actor.device)
+    st = _lib.jp_obrs_lambda_for_budget_batch(_p(actor), _p(policy), T, V, stride, dt, float(target), _p(out),
+                                              _p(buf.workspace), buf.workspace.numel(), _p(scratch),
+                                              scratch.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
     return out

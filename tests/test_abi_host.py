@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert set(obrs.EXPORTS) == set(names)
-    assert obrs.jp_obrs_abi_version() == 6
+    assert obrs.jp_obrs_abi_version() == 7
 
 
 def test_struct_layouts_match_header():

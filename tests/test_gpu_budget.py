@@ -129,3 +129,80 @@ def test_bad_arguments():
         obrs.jp_obrs_lambda_for_budget(w.actor, w.policy, 0.5, small)
     assert e.value.status == obrs.JP_ERR_WORKSPACE
     torch.cuda.synchronize()
+
+
+# ---- one lambda for the whole batch: mean_t Z_t(lambda) = abar ---------------------------------------
+
+def _zbar(w, lam, rows_per_step=256):
+    """(1/n) sum_t Z_t(lambda) over the valid rows, float64 with torch, a slab of rows at a time."""
+    tot, n = 0.0, 0
+    for r0 in range(0, w.T, rows_per_step):
+        sl = slice(r0, r0 + rows_per_step)
+        ok = w.sampled_ids[sl] >= 0
+        if not bool(ok.any()):
+            continue
+        q = torch.softmax(w.actor[sl][ok].double(), dim=1)
+        p = torch.softmax(w.policy[sl][ok].double(), dim=1)
+        tot += float(torch.minimum(q, p / lam).sum())
+        n += int(ok.sum())
+    return tot / n
+
+
+def _check_batch(w, target, oracle=True):
+    buf = obrs.run_workload(w, 0)
+    lam = float(obrs.jp_obrs_lambda_for_budget_batch(w.actor, w.policy, target, buf).cpu()[0])
+    tol = pu.TOL[w.actor.dtype]
+    zmax = _zbar(w, 1e-30)
+    assert abs(_zbar(w, lam) - min(target, zmax)) <= tol * target, (target, lam)
+    if oracle:
+        want = orc.lambda_for_budget_batch(wl.logits_to_numpy(w.actor), wl.logits_to_numpy(w.policy),
+                                           w.sampled_ids.cpu().numpy(), target)
+        # condition number of the problem from the slope of the mean: d lambda / lambda = -cond d abar / abar
+        eps = 1e-4
+        slope = (_zbar(w, want * (1 + eps)) - _zbar(w, want * (1 - eps))) / (2 * eps)     # dZ / dlog(lambda) < 0
+        cond = target / max(-slope, 1e-300)
+        if cond <= 100.0:
+            assert abs(lam - want) <= tol * (1.0 + cond) * want, (target, lam, want, cond)
+    return lam
+
+
+@pytest.mark.parametrize("target", [1.0, 0.9, 0.5, 0.1, 1e-3])
+def test_batch_tiny_config_fp32(target):
+    _say(f"batch budget: tiny fp32 T=64 V=1024 abar={target}")
+    _check_batch(wl.tiny(DEV), target)
+
+
+def test_batch_rollout_shape_bf16_with_padding():
+    _say("batch budget: bf16 T=24 V=151936, per-row noise, padding rows")
+    w = wl.make_logits(24, wl.QWEN3_VOCAB, torch.bfloat16, seed=wl.BASE_SEED + 3, device=DEV,
+                       noise_sigma_range=(0.1, 3.0), pad_every=6).with_params(k=8)
+    prev = None
+    for target in (0.8, 0.4, 0.05):
+        lam = _check_batch(w, target)
+        assert prev is None or lam > prev
+        prev = lam
+
+
+def test_batch_one_valid_row_equals_the_per_row_solver():
+    _say("batch budget: a single valid row")
+    w = wl.make_logits(5, 4100, torch.float32, seed=12, device=DEV, noise_sigma=1.0).with_params(k=8)
+    w.sampled_ids[:] = -1
+    w.sampled_ids[3] = 17
+    buf = obrs.run_workload(w, 0)
+    lam_b = float(obrs.jp_obrs_lambda_for_budget_batch(w.actor, w.policy, 0.3, buf).cpu()[0])
+    lam_r = float(obrs.jp_obrs_lambda_for_budget(w.actor, w.policy, 0.3, buf).cpu()[3])
+    assert lam_b == pytest.approx(lam_r, rel=1e-5)
+    w.sampled_ids[:] = -1                                     # and none at all
+    buf = obrs.run_workload(w, 0)
+    assert np.isnan(float(obrs.jp_obrs_lambda_for_budget_batch(w.actor, w.policy, 0.3, buf).cpu()[0]))
+
+
+def test_batch_full_size_budget_is_met():
+    T, target = 8192, 0.6
+    _say(f"batch budget: bf16 T={T} V=151936 full size abar={target}: mean Z(lambda) = abar")
+    w = wl.rollout(DEV, T=T)
+    lam = _check_batch(w, target, oracle=False)
+    # repeatable to the bit: fixed-point sums do not depend on the order of the atomics
+    buf = obrs.run_workload(w, 0)
+    again = float(obrs.jp_obrs_lambda_for_budget_batch(w.actor, w.policy, target, buf).cpu()[0])
+    assert again == lam
