@@ -986,14 +986,47 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
     const float Aq = (float)(A.lse_q[t] * LOG2E_D);
     const float Ap = (float)((A.lse_p[t] + log((double)A.lambda)) * LOG2E_D);
     float s0 = 0.f, s1 = 0.f;
-    for (uint32_t c = lane; c < nchunks; c += WAVE) {
-        float fq[VEC], fp[VEC];
-        load_chunk<ET>(rowq, c, nfull, tail, fq);
-        load_chunk<ET>(rowp, c, nfull, tail, fp);
+    auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
 #pragma unroll
         for (int j = 0; j < VEC; j += 2) {
             s0 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j], LOG2E_F, -Aq), __builtin_fmaf(fp[j], LOG2E_F, -Ap)));
             s1 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j + 1], LOG2E_F, -Aq), __builtin_fmaf(fp[j + 1], LOG2E_F, -Ap)));
+        }
+    };
+    const uint32_t nit = nfull / WAVE;                      // iterations in which every lane has a full chunk
+    if (nit > 0) {
+        constexpr int D = 3;                                // non-temporal loads in flight per tensor and lane
+        const uint32_t last = nit - 1;
+        u32x4 wq[D], wp[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const uint32_t n = ((uint32_t)d < last ? (uint32_t)d : last) * WAVE + lane;
+            wq[d] = stream_load(as_global_vec(rowq) + n);
+            wp[d] = stream_load(as_global_vec(rowp) + n);
+        }
+        for (uint32_t it = 0; it < nit; it += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const u32x4 cq = wq[d], cp = wp[d];
+                const uint32_t n = (it + D + d < last ? it + D + d : last) * WAVE + lane;
+                wq[d] = stream_load(as_global_vec(rowq) + n);
+                wp[d] = stream_load(as_global_vec(rowp) + n);
+                if (d == 0 || it + d < nit) {
+                    float fq[VEC], fp[VEC];
+                    ET::unpack(cq, fq);
+                    ET::unpack(cp, fp);
+                    account(fq, fp);
+                }
+            }
+        }
+    }
+    {
+        const uint32_t c = nit * WAVE + lane;
+        if (c < nchunks) {
+            float fq[VEC], fp[VEC];
+            load_chunk<ET>(rowq, c, nfull, tail, fq);
+            load_chunk<ET>(rowp, c, nfull, tail, fp);
+            account(fq, fp);
         }
     }
     const double Z = wave_sum((double)s0 + (double)s1);
