@@ -337,5 +337,17 @@ def rows_stored(policy: np.ndarray, ids_q, logq_ids, logq_x, x, u, lam: float, k
     return Rows(out, ids, kp, used)
 
 
+def lm_head_logits(H: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """Logits of the fused lm_head form as the oracle defines them: the exact float64 product of the
+    stored bf16 values, H [n, d] x W [d, V] (both given as bf16 bits in uint16, or as floats); nothing is
+    rounded before the OBRS computation."""
+    def wide(a):
+        a = np.asarray(a)
+        if a.dtype == np.uint16:
+            return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        return a.astype(np.float64)
+    return wide(H) @ wide(W)
+
+
 def max_threads() -> int:
     return lib().jpo_max_threads()

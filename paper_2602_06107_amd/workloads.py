@@ -223,13 +223,3 @@ def lm_head(T: int = 16384, V: int = QWEN3_VOCAB, d_actor: int = 2048, d_policy:
         ids = torch.where(upd, a + v0, ids)
     uni = torch.rand(T, generator=gen, device=dev, dtype=torch.float32)
     return LmHeadWorkload(name, Ha, Wa, Hp, Wp, ids.to(torch.int32), uni, k=k)
-
-
-def lm_head_logits_float64(w: LmHeadWorkload, rows) -> tuple:
-    """Exact-input float64 logits of the given rows: (actor [n, V], policy [n, V]) as numpy arrays."""
-    r = torch.as_tensor(rows, device=w.H_actor.device)
-    Ha = w.H_actor[r].cpu().double().numpy()
-    Hp = w.H_policy[r].cpu().double().numpy()
-    Wa = w.W_actor.cpu().double().numpy()
-    Wp = w.W_policy.cpu().double().numpy()
-    return Ha @ Wa, Hp @ Wp

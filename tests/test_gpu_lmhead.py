@@ -34,7 +34,9 @@ def _run(w, flags=0, vocab_chunk=0):
 
 
 def _check(w, buf, rows, flags=0, batch=True):
-    lq, lp = wl.lm_head_logits_float64(w, rows)
+    r = torch.as_tensor(rows, device=w.H_actor.device)
+    lq = orc.lm_head_logits(wl.logits_to_numpy(w.H_actor[r]), wl.logits_to_numpy(w.W_actor))
+    lp = orc.lm_head_logits(wl.logits_to_numpy(w.H_policy[r]), wl.logits_to_numpy(w.W_policy))
     x = w.sampled_ids.cpu().numpy()[rows]
     u = w.uniforms.cpu().numpy()[rows]
     R = orc.rows(lq, lp, x, u, w.lam, w.k)
