@@ -167,3 +167,37 @@ def test_empty_batch_and_all_padding():
     buf = obrs.run_workload(w0)
     torch.cuda.synchronize()
     assert buf.stats().error_flags == obrs.JP_DATA_ERR_EMPTY
+
+
+def test_forward_can_be_captured_in_a_hip_graph():
+    _say("bf16 T=256 V=20000: forward captured in a graph, replayed three times with eager work between")
+    w = wl.make_logits(256, 20000, torch.bfloat16, seed=21, device=DEV).with_params(k=32, lam=1.0)
+    flags = ALL_FLAGS
+    buf = obrs.alloc_buffers(w.T, w.V, w.k, obrs.JP_BF16, flags, DEV)
+
+    def step():
+        obrs.jp_obrs_forward(w.actor, w.policy, w.sampled_ids, w.uniforms, None, w.lam, w.k, w.c1, w.c2,
+                             flags, buf)
+
+    step()
+    torch.cuda.synchronize()
+    ref = {n: t.clone() for n, t in buf.tensors.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                            # warm-up on the capture side
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in buf.tensors.values():
+            t.zero_()                                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in ref:
+            same = torch.equal(buf.tensors[n], ref[n]) or (
+                ref[n].is_floating_point() and torch.equal(torch.nan_to_num(buf.tensors[n]), torch.nan_to_num(ref[n])))
+            assert same, (rep, n)
