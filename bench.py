@@ -53,9 +53,13 @@ def bench_lm_head(args, torch, obrs, wl, dev):
     nbytes = obrs.jp_obrs_lmhead_workspace_bytes(T, V, da, dp, w.k, args.vocab_chunk)
     buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, 0, dev, workspace_bytes=nbytes)
 
+    Wa, Wp, lm_flags = w.W_actor, w.W_policy, 0
+    if args.w_vocab_major:
+        Wa, Wp, lm_flags = w.W_actor.t().contiguous(), w.W_policy.t().contiguous(), obrs.JP_FLAG_W_VOCAB_MAJOR
+
     def step():
-        obrs.jp_obrs_forward_lmhead(w.H_actor, w.W_actor, w.H_policy, w.W_policy, w.sampled_ids,
-                                    w.uniforms, None, w.lam, w.k, w.c1, w.c2, 0, buf, args.vocab_chunk)
+        obrs.jp_obrs_forward_lmhead(w.H_actor, Wa, w.H_policy, Wp, w.sampled_ids,
+                                    w.uniforms, None, w.lam, w.k, w.c1, w.c2, lm_flags, buf, args.vocab_chunk)
 
     for _ in range(args.warmup):
         step()
@@ -73,8 +77,9 @@ def bench_lm_head(args, torch, obrs, wl, dev):
         "value": T * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
-        "config": {"workload": "lm_head: T=%d, d_actor=%d, d_policy=%d, V=%d, k=%d, lambda=%g, chunk=%d"
-                               % (T, da, dp, V, w.k, w.lam, args.vocab_chunk or 4096),
+        "config": {"workload": "lm_head: T=%d, d_actor=%d, d_policy=%d, V=%d, k=%d, lambda=%g, chunk=%d, W as %s"
+                               % (T, da, dp, V, w.k, w.lam, args.vocab_chunk or 4096,
+                                  "[V, d]" if args.w_vocab_major else "[d, V]"),
                    "kappa": st.kappa, "alpha_hat": st.alpha_hat},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
@@ -97,6 +102,8 @@ def main():
                     help="JP_FLAG_* bits for the timed calls (default 0: the hot path as quoted; "
                          "8 adds the per-token distillation KL to the same sweep)")
     ap.add_argument("--vocab-chunk", type=int, default=0, help="lm_head workload: columns per chunk")
+    ap.add_argument("--w-vocab-major", action="store_true",
+                    help="lm_head workload: hand the weights over as [V, d] (no transpose inside the call)")
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="also run this many plain elementwise passes (bf16 negate) over the actor tensor: "
                          "a kernel of known HBM traffic that scales rocprofv3 FETCH_SIZE / WRITE_SIZE")

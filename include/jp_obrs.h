@@ -61,7 +61,10 @@ enum {
     JP_FLAG_EXACT_Z = 1,        /* also compute Z over the whole vocabulary (second sweep)  */
     JP_FLAG_TOPK_LOGPROBS = 2,  /* also write log-probabilities of the two top-k lists      */
     JP_FLAG_ALPHA_EXPECTED = 4, /* alpha_hat := mean_t a_t instead of accepted/proposed     */
-    JP_FLAG_DISTILL_KL = 8      /* also compute the per-token distillation term KL(p || q)   */
+    JP_FLAG_DISTILL_KL = 8,     /* also compute the per-token distillation term KL(p || q)   */
+    JP_FLAG_W_VOCAB_MAJOR = 16  /* jp_obrs_forward_lmhead only: W_* are [V, d] (one row per token
+                                   of the vocabulary, the layout of an output embedding) instead
+                                   of [d, V]; no transpose is then needed                     */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */
@@ -160,8 +163,9 @@ jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *r
  * stage without ever materialising [T, V].  Everything else (Sec. 4.1, 4.4.1, 4.4.2, Alg. 1
  * steps 2-3) is as in jp_obrs_forward.
  *   H_actor  [T, d_actor]  bf16 row-major, contiguous, 16-byte aligned; d_actor  % 64 == 0
- *   W_actor  [d_actor, V]  bf16 row-major, contiguous
- *   H_policy [T, d_policy], W_policy [d_policy, V] likewise
+ *   W_actor  [d_actor, V]  bf16 row-major, contiguous; with JP_FLAG_W_VOCAB_MAJOR [V, d_actor]
+ *            row-major, contiguous, 16-byte aligned
+ *   H_policy [T, d_policy], W_policy [d_policy, V] (or [V, d_policy]) likewise
  *   vocab_chunk: columns per chunk (rounded up to a multiple of 256); 0 = default (4096)
  * JP_FLAG_EXACT_Z is not available here (JP_ERR_UNSUPPORTED): the logits are gone after one pass.
  * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit chunks [T, chunk], the transposed

@@ -254,6 +254,28 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
     }
 }
 
+// Wt[n, :] = W[v0 + n, :] for n < ncols, zero rows up to npad: the vocabulary-major weight layout needs
+// no transpose, only this padded copy for the last, partial chunk.  d is a multiple of 64.
+__global__ __launch_bounds__(256) void copy_rows_chunk_kernel(const u32x4 *__restrict__ W, int d16, int64_t v0,
+                                                              int ncols, int npad, u32x4 *__restrict__ Wt)
+{
+    const int64_t total = (int64_t)npad * d16;               // 16-byte pieces
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t n = i / d16;
+        Wt[i] = n < ncols ? W[(v0 + n) * d16 + (i - n * d16)] : u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+hipError_t launch_copy_rows_chunk(const void *W, int d, int64_t v0, int ncols, int npad, void *Wt, hipStream_t st)
+{
+    const int d16 = d / 8;
+    const int64_t total = (int64_t)npad * d16;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(copy_rows_chunk_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4 *)W, d16, v0, ncols, npad,
+                       (u32x4 *)Wt);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0, int ncols, int npad,
                                   void *Wt, hipStream_t st)
 {

@@ -6,7 +6,8 @@
 
 namespace {
 
-constexpr uint32_t KNOWN_FLAGS = JP_FLAG_EXACT_Z | JP_FLAG_TOPK_LOGPROBS | JP_FLAG_ALPHA_EXPECTED | JP_FLAG_DISTILL_KL;
+constexpr uint32_t KNOWN_FLAGS = JP_FLAG_EXACT_Z | JP_FLAG_TOPK_LOGPROBS | JP_FLAG_ALPHA_EXPECTED | JP_FLAG_DISTILL_KL |
+                                 JP_FLAG_W_VOCAB_MAJOR;
 constexpr size_t ALIGN = 256;
 
 size_t round_up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
@@ -208,6 +209,8 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
     if (prm->flags & JP_FLAG_EXACT_Z) return JP_ERR_UNSUPPORTED;   // needs a second pass over logits that are gone
     if (T > 0 && (!H_actor || !W_actor || !H_policy || !W_policy || !sampled_ids)) return JP_ERR_NULL;
     if (!aligned16(H_actor) || !aligned16(H_policy) || ((uintptr_t)W_actor & 1) || ((uintptr_t)W_policy & 1)) return JP_ERR_ALIGN;
+    const bool vmajor = (prm->flags & JP_FLAG_W_VOCAB_MAJOR) != 0;
+    if (vmajor && (!aligned16(W_actor) || !aligned16(W_policy))) return JP_ERR_ALIGN;
     if (!workspace || workspace_bytes < pl.bytes) return JP_ERR_WORKSPACE;
     if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
@@ -244,8 +247,19 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
         for (int64_t j = 0; j < pl.nchunks; ++j) {
             const int64_t v0 = j * pl.chunk;
             const int ncols = (int)((V - v0) < pl.chunk ? (V - v0) : pl.chunk);
-            if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
-            if (jp::launch_transpose_chunk(W_actor, V, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+            if (!vmajor) {
+                if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_transpose_chunk(W_actor, V, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+            } else if (ncols == (int)pl.npad) {
+                // [V, d] weights: a full chunk of rows is already the GEMM's second operand
+                g.Bt[0] = (const char *)W_policy + (size_t)v0 * (size_t)d_policy * 2;
+                g.Bt[1] = (const char *)W_actor + (size_t)v0 * (size_t)d_actor * 2;
+            } else {
+                if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_copy_rows_chunk(W_actor, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+                g.Bt[0] = base + pl.off_wt_p;
+                g.Bt[1] = base + pl.off_wt_a;
+            }
             if (jp::launch_gemm_pair(g, st) != hipSuccess) return JP_ERR_HIP;
             a.V = ncols; a.id_base = v0; a.carry_in = j > 0; a.carry_out = j + 1 < pl.nchunks;
             if (jp::launch_rows_carry(a, st) != hipSuccess) return JP_ERR_HIP;

@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("JP_OBRS_LIB", os.path.join(_PKG, "libjp_obrs.so"))   
 JP_K_MAX = 256
 JP_F32, JP_BF16 = 0, 1
 JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED, JP_FLAG_DISTILL_KL = 1, 2, 4, 8
+JP_FLAG_W_VOCAB_MAJOR = 16
 JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
 JP_TAIL_DROP, JP_TAIL_KTH, JP_TAIL_REST = 0, 1, 2
 JP_F_TRUNCATE, JP_F_IDENTITY, JP_F_BAND = 0, 1, 2
@@ -356,8 +357,13 @@ def jp_obrs_forward_lmhead(H_actor, W_actor, H_policy, W_policy, sampled_ids, un
             raise ValueError("hidden states and weights must be contiguous 2-D bfloat16 tensors")
     T, d_a = H_actor.shape
     d_p = H_policy.shape[1]
-    V = W_actor.shape[1]
-    if H_policy.shape[0] != T or W_actor.shape[0] != d_a or tuple(W_policy.shape) != (d_p, V):
+    if flags & JP_FLAG_W_VOCAB_MAJOR:                        # weights as [V, d]
+        V = W_actor.shape[0]
+        ok = W_actor.shape[1] == d_a and tuple(W_policy.shape) == (V, d_p)
+    else:                                                    # weights as [d, V]
+        V = W_actor.shape[1]
+        ok = W_actor.shape[0] == d_a and tuple(W_policy.shape) == (d_p, V)
+    if H_policy.shape[0] != T or not ok:
         raise ValueError("shape mismatch between hidden states and weights")
     prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
     st = _lib.jp_obrs_forward_lmhead(_p(H_actor), d_a, _p(W_actor), _p(H_policy), d_p, _p(W_policy), T, V,

@@ -23,7 +23,8 @@ TIE = 1e-4
 
 
 def _run(w, flags=0, vocab_chunk=0):
-    T, V = w.T, w.V
+    T = w.T
+    V = w.W_actor.shape[0] if flags & obrs.JP_FLAG_W_VOCAB_MAJOR else w.V
     nbytes = obrs.jp_obrs_lmhead_workspace_bytes(T, V, w.H_actor.shape[1], w.H_policy.shape[1], w.k, vocab_chunk)
     assert nbytes > 0
     buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, flags, DEV, workspace_bytes=nbytes)
@@ -96,6 +97,23 @@ def test_lmhead_small_shapes(T, V, da, dp, k, chunk):
     flags = obrs.JP_FLAG_TOPK_LOGPROBS | obrs.JP_FLAG_DISTILL_KL
     buf = _run(w, flags, chunk)
     _check(w, buf, np.arange(T), flags)
+
+
+@pytest.mark.parametrize("T,V,da,dp,k,chunk", [
+    (48, 3000, 128, 192, 16, 512),       # full chunks used in place, the ragged last one copied and padded
+    (17, 700, 64, 128, 64, 0),           # single, partial chunk
+    (40, 2048, 64, 64, 32, 1024),        # V a multiple of the chunk: nothing is copied
+])
+def test_lmhead_vocab_major_weights_give_the_same_bits(T, V, da, dp, k, chunk):
+    print(f"lm_head [V, d] weights T={T} V={V} d=({da},{dp}) k={k} chunk={chunk}", flush=True)
+    w = wl.lm_head(T, V, da, dp, DEV, seed=200 + T, k=k)
+    flags = obrs.JP_FLAG_TOPK_LOGPROBS
+    ref = _run(w, flags, chunk)
+    wt = w.with_params(W_actor=w.W_actor.t().contiguous(), W_policy=w.W_policy.t().contiguous())
+    got = _run(wt, flags | obrs.JP_FLAG_W_VOCAB_MAJOR, chunk)
+    for n in ref.tensors:
+        assert torch.equal(got.tensors[n], ref.tensors[n]) or n == "stats", n
+    assert got.stats().kappa == ref.stats().kappa
 
 
 def test_lmhead_matches_materialised_path():
