@@ -1158,16 +1158,19 @@ __device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp,
         for (int j = 0; j < VEC; ++j) {
             const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
             const float d = ap - aq;
-            const float q = __builtin_amdgcn_exp2f(aq), p = __builtin_amdgcn_exp2f(ap);
-            pbf += d < lo ? p : 0.f;                    // at or below every lambda of the bracket
-            qaf += d >= hi ? q : 0.f;                   // above every lambda of the bracket
+            // a token outside the bracket needs only one of its two probabilities: p below it, q above
+            const bool below = d < lo;
+            const float one = __builtin_amdgcn_exp2f(below ? ap : aq);
+            pbf += below ? one : 0.f;                   // at or below every lambda of the bracket
+            qaf += d >= hi ? one : 0.f;                 // above every lambda of the bracket
             if (d >= lo && d < hi) {                    // (both probabilities 0 give NaN: no mass)
                 int b = (int)((d - lo) * inv_w);
                 b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
-                atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(q));
-                atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(p));
+                atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(one));
+                atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(__builtin_amdgcn_exp2f(ap)));
             }
-            if (first_pass) dmin = (q > 0.f && p > 0.f) ? fminf(dmin, d) : dmin;
+            // the smallest ratio among tokens that both models can emit (finite d)
+            if (first_pass) dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
         }
         pb += (double)pbf;
         qa += (double)qaf;
