@@ -152,7 +152,10 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
 
 // ---- fused lm_head path ------------------------------------------------------------------------
 
+constexpr int64_t LM_GROUP = 2;
+
 struct LmheadPlan {
+    int64_t group, ldc;
     int64_t chunk, npad, nchunks;
     size_t off_state, off_wt_p, off_wt_a, off_lp, off_lq, bytes;
     size_t state_stride;
@@ -174,8 +177,12 @@ bool plan_lmhead(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_
     p.off_state = off; off += round_up(n * p.state_stride);
     p.off_wt_p = off; off += round_up((size_t)c * (size_t)d_policy * 2);
     p.off_wt_a = off; off += round_up((size_t)c * (size_t)d_actor * 2);
-    p.off_lp = off; off += round_up(n * (size_t)c * 4);
-    p.off_lq = off; off += round_up(n * (size_t)c * 4);
+    // the logit buffers hold LM_GROUP chunks side by side: the row stage runs once per group, which
+    // spreads its per-row fixed cost (record read/write, list merge) over more columns
+    p.group = p.nchunks < LM_GROUP ? p.nchunks : LM_GROUP;
+    p.ldc = c * p.group;
+    p.off_lp = off; off += round_up(n * (size_t)p.ldc * 4);
+    p.off_lq = off; off += round_up(n * (size_t)p.ldc * 4);
     p.bytes = off;
     return true;
 }
@@ -220,7 +227,7 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
         char *base = (char *)workspace;
         jp::RowArgs a{};
         a.actor = base + pl.off_lq; a.policy = base + pl.off_lp;
-        a.T = T; a.stride = pl.npad; a.ids = sampled_ids; a.uni = uniforms;
+        a.T = T; a.stride = pl.ldc; a.ids = sampled_ids; a.uni = uniforms;
         a.lambda = prm->lambda; a.ln_lambda = log((double)prm->lambda); a.k = prm->k;
         a.accept = out->accept_prob ? out->accept_prob : w.accept;
         a.logq = out->logq ? out->logq : w.logq;
@@ -242,27 +249,41 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
         jp::GemmArgs g{};
         g.A[0] = H_policy; g.Bt[0] = base + pl.off_wt_p; g.C[0] = (float *)(base + pl.off_lp); g.K[0] = (int)d_policy;
         g.A[1] = H_actor; g.Bt[1] = base + pl.off_wt_a; g.C[1] = (float *)(base + pl.off_lq); g.K[1] = (int)d_actor;
-        g.M = (int)T; g.N = (int)pl.npad; g.nproblems = 2; g.ldc = pl.npad;
+        g.M = (int)T; g.N = (int)pl.npad; g.nproblems = 2; g.ldc = pl.ldc;
+        float *const c_policy = (float *)(base + pl.off_lp), *const c_actor = (float *)(base + pl.off_lq);
+        int64_t group_base = 0, group_cols = 0, groups_done = 0;
 
         for (int64_t j = 0; j < pl.nchunks; ++j) {
             const int64_t v0 = j * pl.chunk;
             const int ncols = (int)((V - v0) < pl.chunk ? (V - v0) : pl.chunk);
+            // the last chunk is multiplied only up to its own width rounded to the column tile
+            const int nthis = (ncols + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
+            g.N = nthis;
+            const int64_t slot = j % pl.group;                // where this chunk sits inside the group buffer
+            g.C[0] = c_policy + slot * pl.chunk;
+            g.C[1] = c_actor + slot * pl.chunk;
+            if (slot == 0) { group_base = v0; group_cols = 0; }
+            group_cols += ncols;
             if (!vmajor) {
-                if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
-                if (jp::launch_transpose_chunk(W_actor, V, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
-            } else if (ncols == (int)pl.npad) {
-                // [V, d] weights: a full chunk of rows is already the GEMM's second operand
+                if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_transpose_chunk(W_actor, V, (int)d_actor, v0, ncols, nthis, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+            } else if (ncols == nthis) {
+                // [V, d] weights: a chunk of whole column tiles is already the GEMM's second operand
                 g.Bt[0] = (const char *)W_policy + (size_t)v0 * (size_t)d_policy * 2;
                 g.Bt[1] = (const char *)W_actor + (size_t)v0 * (size_t)d_actor * 2;
             } else {
-                if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, (int)pl.npad, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
-                if (jp::launch_copy_rows_chunk(W_actor, (int)d_actor, v0, ncols, (int)pl.npad, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_copy_rows_chunk(W_actor, (int)d_actor, v0, ncols, nthis, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
                 g.Bt[0] = base + pl.off_wt_p;
                 g.Bt[1] = base + pl.off_wt_a;
             }
             if (jp::launch_gemm_pair(g, st) != hipSuccess) return JP_ERR_HIP;
-            a.V = ncols; a.id_base = v0; a.carry_in = j > 0; a.carry_out = j + 1 < pl.nchunks;
-            if (jp::launch_rows_carry(a, st) != hipSuccess) return JP_ERR_HIP;
+            const bool last = j + 1 == pl.nchunks;
+            if (slot + 1 == pl.group || last) {               // the group is complete: one row-stage launch over it
+                a.V = group_cols; a.id_base = group_base; a.carry_in = groups_done > 0; a.carry_out = !last;
+                if (jp::launch_rows_carry(a, st) != hipSuccess) return JP_ERR_HIP;
+                ++groups_done;
+            }
         }
     }
     return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes, st,
