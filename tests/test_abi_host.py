@@ -99,3 +99,87 @@ def test_status_strings():
         assert msg and msg not in seen
         seen.add(msg)
     assert obrs.jp_status_string(99) == "unknown status"
+
+
+# ---- the other entry points: everything below is rejected by host-side validation (fake device
+# addresses, never dereferenced), so nothing is launched ------------------------------------------------
+
+A_, P_, X_, U_, O_, W_ = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x100000
+
+
+def test_workspace_queries_of_the_other_entry_points():
+    base = obrs.jp_obrs_workspace_bytes(64, 1024, 8, obrs.JP_F32)
+    assert obrs.jp_obrs_forward3_workspace_bytes(64, 1024, 8, obrs.JP_F32) == base + 256
+    assert obrs.jp_obrs_forward3_workspace_bytes(-1, 1024, 8, obrs.JP_F32) == 0
+    assert obrs.raw().jp_obrs_budget_scratch_bytes() >= 1088
+    lm = obrs.jp_obrs_lmhead_workspace_bytes
+    assert lm(256, 8192, 128, 256, 8, 4096) > base
+    assert lm(256, 8192, 128, 256, 8, 4096) >= 2 * 256 * 8192 * 4          # two logit buffers of two chunks
+    assert lm(256, 8192, 100, 256, 8, 4096) == 0                            # d not a multiple of 64
+    assert lm(256, 8192, 128, 256, 0, 4096) == 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), None),                                          # baseline of this table: only the workspace is wrong
+    (dict(tail=3), obrs.JP_ERR_PARAM),
+    (dict(flags=obrs.JP_FLAG_EXACT_Z), obrs.JP_ERR_UNSUPPORTED),
+    (dict(flags=obrs.JP_FLAG_DISTILL_KL), obrs.JP_ERR_UNSUPPORTED),
+    (dict(ids_q=None), obrs.JP_ERR_NULL),
+    (dict(policy=P_ + 2), obrs.JP_ERR_ALIGN),
+    (dict(k=0), obrs.JP_ERR_PARAM),
+])
+def test_forward_stored_rejections(kw, want):
+    a = dict(policy=P_, ids_q=0x60000, lq=0x70000, lqx=0x80000, k=8, flags=0, tail=1, ws_bytes=1 << 20)
+    a.update(kw)
+    prm = obrs.Params(1.0, a["k"], 3.0, 3.0, a["flags"])
+    out = obrs.Outputs()
+    st = obrs.raw().jp_obrs_forward_stored(a["policy"], 4, 1024, 1024, obrs.JP_F32, a["ids_q"], a["lq"], a["lqx"],
+                                           X_, U_, None, C.byref(prm), a["tail"], C.byref(out), W_,
+                                           16 if want is None else a["ws_bytes"], None)
+    assert st == (obrs.JP_ERR_WORKSPACE if want is None else want)
+
+
+def test_distill_grad_token_logprob_and_budget_rejections():
+    lib = obrs.raw()
+    g = lambda **k: lib.jp_obrs_distill_grad(k.get("actor", A_), P_, 4, 1024, 1024, obrs.JP_F32, None,
+                                             C.c_float(k.get("scale", 1.0)), k.get("grad", O_), k.get("gs", 1024),
+                                             k.get("gdt", obrs.JP_BF16), W_, k.get("wsb", 16), None)
+    assert g() == obrs.JP_ERR_WORKSPACE
+    assert g(grad=None) == obrs.JP_ERR_NULL
+    assert g(grad=O_ + 8) == obrs.JP_ERR_ALIGN
+    assert g(gs=1000) == obrs.JP_ERR_SHAPE
+    assert g(gdt=4) == obrs.JP_ERR_UNSUPPORTED
+    assert g(scale=float("inf")) == obrs.JP_ERR_PARAM
+    t = lambda **k: lib.jp_obrs_token_logprob(k.get("logits", P_), k.get("T", 4), k.get("V", 1024), k.get("stride", 1024),
+                                              k.get("dt", obrs.JP_F32), k.get("ids", X_), k.get("out", O_), None)
+    assert t(T=0) == obrs.JP_OK                               # nothing to do, nothing launched
+    assert t(out=None) == obrs.JP_ERR_NULL
+    assert t(logits=P_ + 4) == obrs.JP_ERR_ALIGN
+    assert t(stride=1000) == obrs.JP_ERR_SHAPE
+    assert t(dt=3) == obrs.JP_ERR_UNSUPPORTED
+    b = lambda **k: lib.jp_obrs_lambda_for_budget(A_, P_, 4, 1024, 1024, obrs.JP_F32, k.get("rt", None),
+                                                  C.c_float(k.get("target", 0.5)), k.get("out", O_), W_,
+                                                  k.get("wsb", 16), None)
+    assert b() == obrs.JP_ERR_WORKSPACE
+    assert b(target=0.0) == obrs.JP_ERR_PARAM and b(target=1.5) == obrs.JP_ERR_PARAM
+    assert b(target=0.0, rt=0x90000) == obrs.JP_ERR_WORKSPACE  # per-row budgets are checked on the device
+    assert b(out=None) == obrs.JP_ERR_NULL
+    bb = lambda **k: lib.jp_obrs_lambda_for_budget_batch(A_, P_, 4, 1024, 1024, obrs.JP_F32, C.c_float(k.get("target", 0.5)),
+                                                         k.get("out", O_), W_, k.get("wsb", 1 << 20),
+                                                         k.get("scratch", 0xA0000), k.get("sb", 16), None)
+    assert bb() == obrs.JP_ERR_WORKSPACE                      # scratch too small
+    assert bb(out=None) == obrs.JP_ERR_NULL
+    assert bb(target=2.0) == obrs.JP_ERR_PARAM
+    assert bb(scratch=None, sb=4096) == obrs.JP_ERR_WORKSPACE
+
+
+def test_forward3_rejections():
+    lib = obrs.raw()
+    prm = obrs.Params(1.0, 8, 3.0, 3.0, 0)
+    out = obrs.Outputs()
+    f = lambda **k: lib.jp_obrs_forward3(A_, k.get("new", P_), k.get("ref", 0x60000), k.get("tir", 0), 4, 1024, 1024,
+                                         obrs.JP_F32, X_, U_, C.byref(prm), C.byref(out), W_, k.get("wsb", 16), None)
+    assert f() == obrs.JP_ERR_WORKSPACE
+    assert f(ref=None) == obrs.JP_ERR_NULL
+    assert f(new=None, wsb=1 << 20) == obrs.JP_ERR_NULL       # the new policy is needed when it is the target
+    assert f(tir=1, new=None) == obrs.JP_ERR_WORKSPACE        # ... and is not read when p_ref is the target
