@@ -87,7 +87,7 @@ struct GradArgs {
     float scale;
     void *grad;                       // [T, V], `grad_stride` elements between rows
     int64_t grad_stride;
-    uint32_t seg_batches, segs;       // set by the launcher: batches of 1024 chunks per workgroup, workgroups per row
+    uint32_t seg_chunks, segs;        // set by the launcher: pieces per workgroup, workgroups per row
 };
 
 struct LogprobArgs {
