@@ -5,7 +5,8 @@
 //   * transpose_chunk_kernel: W[d, V] (vocabulary contiguous) -> Wt[n, d] for the columns of one
 //     chunk, so that both GEMM operands are contiguous along the contraction dimension;
 //   * gemm_tn_kernel: C[M, N] = A[M, K] * Bt[N, K]^T with 256x256x64 workgroup tiles, XOR-swizzled
-//     LDS tiles, register-staged double buffering, 2x2 waves of 128x128 (4x4 MFMA blocks each).
+//     LDS tiles filled straight from global memory round a five-slot ring, 2x2 waves of 128x128
+//     (4x4 MFMA blocks each).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256) void transpose_chunk_kernel(const uint16_t *__
 // -------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_tn_kernel(GemmArgs G)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // NS stages x (A tile, B tile)
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // ring of NU operand-tile slots
     const int z = blockIdx.z;
     const unsigned char *A = (const unsigned char *)G.A[z];
     const unsigned char *B = (const unsigned char *)G.Bt[z];

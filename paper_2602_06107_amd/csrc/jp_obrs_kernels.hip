@@ -441,7 +441,7 @@ __device__ __forceinline__ void load_chunk(const char *row, uint32_t c, uint32_t
 // top-k lists so far with both logits of every entry) is read from / written to a per-row record,
 // and only the launch of the last chunk runs the union / normaliser / acceptance step.
 template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false>
-__global__ __launch_bounds__(64, (KC <= 64 ? 8 : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
+__global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
