@@ -1110,9 +1110,10 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
 // Z(lambda) = sum_v min(q_v, p_v / lambda) = abar.  With d_v = log2(p_v / q_v),
 //   Z(2^x) = sum_{d_v > x} q_v + 2^-x sum_{d_v <= x} p_v
 // is non-increasing in x, so the crossing is bracketed by histogram passes: a pass sweeps the row,
-// adds q_v and p_v of the tokens inside the current bracket [lo, hi) to 64 bins (fixed point, so the
-// sums do not depend on the order of the atomics; 8 copies per bin keep same-address collisions
-// to eight lanes) and the mass outside it to two per-lane sums; the bin whose edges straddle abar is
+// adds q_v and p_v of the tokens inside the current bracket [lo, hi) to 64 bins in LDS (float64
+// atomics; the bins belong to this wave alone and the hardware takes the lanes of an instruction in
+// a fixed order, so the sums are reproducible; 8 copies per bin keep same-address collisions to
+// eight lanes) and the mass outside it to two per-lane sums; the bin whose edges straddle abar is
 // the next bracket.  After BUDGET_PASSES passes the bracket is 128 / 64^3 = 4.9e-4 wide in log2
 // lambda and lambda = B / (abar - A) with A the q-mass above it and B the p-mass at or below it;
 // that closed form is exact up to the few tokens whose ratio lies inside the last bracket (their
@@ -1121,25 +1122,29 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
 // =================================================================================================
 constexpr int BUDGET_BINS = 64, BUDGET_COPIES = 8, BUDGET_PASSES = 3;
 constexpr float BUDGET_RANGE = 64.f;                       // first bracket: ratios in [2^-64, 2^64)
-constexpr double BUDGET_FIX = 36028797018963968.0;         // 2^55: fixed-point unit of the bin sums
 
-// x in [0, 1] as an integer multiple of 2^-55, truncated: 31 bits from one conversion, 24 more from
-// the exact remainder (fp32 holds 24 significant bits, so nothing of x is lost above 2^-55).
-__device__ __forceinline__ unsigned long long to_fixed(float x)
+// x in [0, 1] as an integer multiple of 2^-40, truncated: the 24-bit significand shifted into place.
+// (Integer LDS atomics take same-address collisions faster than float64 ones; the first pass, where
+// most tokens share a few bins, uses them.)
+constexpr double BUDGET_FIX40 = 1099511627776.0;           // 2^40
+__device__ __forceinline__ unsigned long long to_fixed40(float x)
 {
-    const uint32_t hi = (uint32_t)(x * 2147483648.0f);                          // floor(x 2^31)
-    const float rem = __builtin_fmaf(-(float)hi, 4.656612873077393e-10f, x);     // x - hi 2^-31, exact
-    const uint32_t lo = (uint32_t)(rem * 36028797018963968.0f);                  // floor(rem 2^55) < 2^24
-    return ((unsigned long long)hi << 24) + lo;
+    const uint32_t bits = __float_as_uint(x);
+    const uint32_t m = (bits & 0x7fffffu) | 0x800000u;      // significand with its leading one
+    uint32_t sh = 142u - (bits >> 23);                      // x = m 2^(e-150): (m 2^32) >> (142 - e) = x 2^40
+    sh = sh < 63u ? sh : 63u;                               // below 2^-40 (and zero): nothing left
+    return ((unsigned long long)m << 32) >> sh;
 }
 
 // One histogram sweep of a row pair for the bracket [lo, hi): q- and p-mass of the tokens inside it
-// go to the LDS bins hq / hp (2^-55 units), the mass outside it to the per-lane sums qa (above) and
-// pb (below); the first pass also tracks the smallest log2 ratio.
-template <class ET>
+// go to the LDS bins hq / hp, the mass outside it to the per-lane sums qa (above) and
+// pb (below).  The first pass (FIRST) covers every ratio: it runs without branches, puts a ratio
+// beyond the range into the nearest edge bin (the later passes sum the mass outside their bracket
+// themselves, so this only has to find the bracket) and tracks the smallest log2 ratio.
+template <class ET, bool FIRST>
 __device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
-                                             float lo, float hi, bool first_pass, unsigned long long *hq,
-                                             unsigned long long *hp, double &qa, double &pb, float &dmin)
+                                             float lo, float hi, double *hq,
+                                             double *hp, double &qa, double &pb, float &dmin)
 {
     constexpr int VEC = ET::VEC;
     const int lane = threadIdx.x;
@@ -1147,33 +1152,59 @@ __device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp,
     const int tail = (int)(V - (int64_t)nfull * VEC);
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
     const int copy = lane & (BUDGET_COPIES - 1);
-    for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0; hp[e] = 0; }
+    for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0.0; hp[e] = 0.0; }   // all bits zero: also integer 0
     lds_sync();
     const float inv_w = (float)BUDGET_BINS / (hi - lo);
     qa = 0.0;
     pb = 0.0;
     auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
-        float pbf = 0.f, qaf = 0.f;                     // this chunk's mass below / above the bracket
+        if constexpr (FIRST) {
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-            const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
-            const float d = ap - aq;
-            // a token outside the bracket needs only one of its two probabilities: p below it, q above
-            const bool below = d < lo;
-            const float one = __builtin_amdgcn_exp2f(below ? ap : aq);
-            pbf += below ? one : 0.f;                   // at or below every lambda of the bracket
-            qaf += d >= hi ? one : 0.f;                 // above every lambda of the bracket
-            if (d >= lo && d < hi) {                    // (both probabilities 0 give NaN: no mass)
+            for (int j = 0; j < VEC; ++j) {
+                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
+                const float d = ap - aq;
+                // A ratio below the range keeps none of its q-mass at any lambda of the range, one
+                // above it pays none of its p-mass; NaN (both probabilities 0) adds two zeros to bin 0.
                 int b = (int)((d - lo) * inv_w);
-                b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
-                atomicAdd(&hq[b * BUDGET_COPIES + copy], to_fixed(one));
-                atomicAdd(&hp[b * BUDGET_COPIES + copy], to_fixed(__builtin_amdgcn_exp2f(ap)));
+                b = b < 0 ? 0 : (b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1);
+                const float qv = d >= lo ? __builtin_amdgcn_exp2f(aq) : 0.f;
+                const float pv = d < hi ? __builtin_amdgcn_exp2f(ap) : 0.f;
+                atomicAdd((unsigned long long *)&hq[b * BUDGET_COPIES + copy], to_fixed40(qv));
+                atomicAdd((unsigned long long *)&hp[b * BUDGET_COPIES + copy], to_fixed40(pv));
+                // the smallest ratio among tokens that both models can emit (finite d)
+                dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
             }
-            // the smallest ratio among tokens that both models can emit (finite d)
-            if (first_pass) dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
+        } else {
+            float pbf = 0.f, qaf = 0.f;                 // this chunk's mass below / above the bracket
+            float dv[VEC], apv[VEC], one[VEC];
+            bool any = false;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq);
+                apv[j] = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
+                dv[j] = apv[j] - aq;
+                // a token outside the bracket needs only one of its two probabilities: p below it, q above
+                const bool below = dv[j] < lo;
+                one[j] = __builtin_amdgcn_exp2f(below ? apv[j] : aq);
+                pbf += below ? one[j] : 0.f;            // at or below every lambda of the bracket
+                qaf += dv[j] >= hi ? one[j] : 0.f;      // above every lambda of the bracket
+                any |= dv[j] >= lo && dv[j] < hi;       // (both probabilities 0 give NaN: no mass)
+            }
+            pb += (double)pbf;
+            qa += (double)qaf;
+            // late passes: the bracket is narrow and most chunks of a wave hold nothing inside it
+            if (__ballot(any)) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    if (dv[j] >= lo && dv[j] < hi) {
+                        int b = (int)((dv[j] - lo) * inv_w);
+                        b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
+                        atomicAdd(&hq[b * BUDGET_COPIES + copy], (double)one[j]);
+                        atomicAdd(&hp[b * BUDGET_COPIES + copy], (double)__builtin_amdgcn_exp2f(apv[j]));
+                    }
+                }
+            }
         }
-        pb += (double)pbf;
-        qa += (double)qaf;
     };
     const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
     if (nit > 0) {
@@ -1212,6 +1243,26 @@ __device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp,
         }
     }
     lds_sync();
+}
+
+// Lane b's bin b summed over its copies: integers in 2^-40 units after the first pass, float64 after the others.
+__device__ __forceinline__ void budget_bin_sums(const double *hq, const double *hp, bool first_pass, double &q, double &p)
+{
+    const int lane = threadIdx.x;
+    if (first_pass) {
+        unsigned long long uq = 0, up = 0;
+#pragma unroll 4
+        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) {
+            uq += ((const unsigned long long *)hq)[lane * BUDGET_COPIES + c2];
+            up += ((const unsigned long long *)hp)[lane * BUDGET_COPIES + c2];
+        }
+        q = (double)uq / BUDGET_FIX40;
+        p = (double)up / BUDGET_FIX40;
+    } else {
+        q = 0.0; p = 0.0;
+#pragma unroll 4
+        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { q += hq[lane * BUDGET_COPIES + c2]; p += hp[lane * BUDGET_COPIES + c2]; }
+    }
 }
 
 // One step of the bracket search, run by a whole wave: lane b brings the q- and p-mass of bin b
@@ -1274,7 +1325,7 @@ __device__ __forceinline__ bool budget_step(double goal, double A_above, double 
 template <class ET>
 __global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
 {
-    __shared__ unsigned long long hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
+    __shared__ double hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
     __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
@@ -1294,14 +1345,14 @@ __global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
     float dmin = __uint_as_float(0x7f800000u);
     for (int pass = 0; pass < BUDGET_PASSES; ++pass) {
         double qa, pb;
-        budget_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, pass == 0, hq, hp, qa, pb, dmin);
+        if (pass == 0) budget_sweep<ET, true>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
+        else budget_sweep<ET, false>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
         const double A_above = wave_sum(qa), B_below = wave_sum(pb);
         // lane b owns bin b
-        unsigned long long uq = 0, up = 0;
-#pragma unroll 4
-        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { uq += hq[lane * BUDGET_COPIES + c2]; up += hp[lane * BUDGET_COPIES + c2]; }
+        double uq, up;
+        budget_bin_sums(hq, hp, pass == 0, uq, up);
         const float dmin_w = pass == 0 ? -uniform_f(wave_max(-dmin)) : 0.f;
-        if (budget_step((double)abar_f, A_above, B_below, (double)uq / BUDGET_FIX, (double)up / BUDGET_FIX, lo, hi,
+        if (budget_step((double)abar_f, A_above, B_below, uq, up, lo, hi,
                         pass, dmin_w, sq_, sp_, lambda))
             break;
     }
@@ -1331,7 +1382,7 @@ __device__ __forceinline__ int float_order_int(float f)
 template <class ET>
 __global__ __launch_bounds__(64, 4) void budget_batch_pass_kernel(BudgetArgs A, BudgetBatchState *S, int pass)
 {
-    __shared__ unsigned long long hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
+    __shared__ double hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     if (S->done || A.rowflag[t] != ROW_OK) return;
@@ -1342,13 +1393,14 @@ __global__ __launch_bounds__(64, 4) void budget_batch_pass_kernel(BudgetArgs A, 
     const float lo = S->lo, hi = S->hi;
     float dmin = __uint_as_float(0x7f800000u);
     double qa, pb;
-    budget_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, pass == 0, hq, hp, qa, pb, dmin);
+    if (pass == 0) budget_sweep<ET, true>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
+    else budget_sweep<ET, false>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
     const double A_above = wave_sum(qa), B_below = wave_sum(pb);
-    unsigned long long uq = 0, up = 0;
-#pragma unroll 4
-    for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { uq += hq[lane * BUDGET_COPIES + c2]; up += hp[lane * BUDGET_COPIES + c2]; }
-    if (uq >> 23) atomicAdd(&S->bq[lane], uq >> 23);        // 2^-55 -> 2^-32 units
-    if (up >> 23) atomicAdd(&S->bp[lane], up >> 23);
+    double dq, dp;
+    budget_bin_sums(hq, hp, pass == 0, dq, dp);
+    const unsigned long long uq = (unsigned long long)(dq * 4294967296.0), up = (unsigned long long)(dp * 4294967296.0);
+    if (uq) atomicAdd(&S->bq[lane], uq);                    // 2^-32 units: integer sums, any order
+    if (up) atomicAdd(&S->bp[lane], up);
     if (pass == 0) dmin = -uniform_f(wave_max(-dmin));
     if (lane == 0) {
         atomicAdd(&S->above, (unsigned long long)(A_above * 4294967296.0));
