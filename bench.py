@@ -61,6 +61,26 @@ def bench_lm_head(args, torch, obrs, wl, dev):
         obrs.jp_obrs_forward_lmhead(w.H_actor, Wa, w.H_policy, Wp, w.sampled_ids,
                                     w.uniforms, None, w.lam, w.k, w.c1, w.c2, lm_flags, buf, args.vocab_chunk)
 
+    stored = args.stored != "none"
+    if stored:
+        # --stored: one head only (jp_obrs_forward_lmhead_stored).  The stored actor side is what
+        # the two-head form itself finds on the same inputs: its top-k(q) ids and log-probabilities.
+        full = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, obrs.JP_FLAG_TOPK_LOGPROBS, dev, workspace_bytes=nbytes)
+        obrs.jp_obrs_forward_lmhead(w.H_actor, Wa, w.H_policy, Wp, w.sampled_ids, w.uniforms, None, w.lam, w.k,
+                                    w.c1, w.c2, lm_flags | obrs.JP_FLAG_TOPK_LOGPROBS, full, args.vocab_chunk)
+        torch.cuda.synchronize()
+        s_ids, s_lq, s_lqx = full.topk_actor.clone(), full.topk_actor_logq.clone(), full.logq.clone()
+        del full, buf
+        rule = {"drop": obrs.JP_TAIL_DROP, "kth": obrs.JP_TAIL_KTH, "rest": obrs.JP_TAIL_REST}[args.stored]
+        nbytes = obrs.jp_obrs_lmhead_stored_workspace_bytes(T, V, dp, w.k, args.vocab_chunk)
+        buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, 0, dev, workspace_bytes=nbytes,
+                                 want=["accept_prob", "mask", "logq", "logp", "logratio", "z_approx", "w_obrs",
+                                       "rho", "union_size", "topk_policy", "stats"])
+
+        def step():
+            obrs.jp_obrs_forward_lmhead_stored(w.H_policy, Wp, s_ids, s_lq, s_lqx, w.sampled_ids, w.uniforms, None,
+                                               w.lam, w.k, w.c1, w.c2, lm_flags, rule, buf, args.vocab_chunk)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -70,10 +90,11 @@ def bench_lm_head(args, torch, obrs, wl, dev):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     st = buf.stats()
-    flops = 2.0 * T * V * (da + dp)
+    flops = 2.0 * T * V * (dp if stored else da + dp)
     tflops = flops * args.steps / wall / 1e12
     print(json.dumps({
-        "metric": "OBRS tokens/sec, fused lm_head form (context, not the headline metric)",
+        "metric": "OBRS tokens/sec, fused lm_head form%s (context, not the headline metric)"
+                  % (", stored actor side (%s)" % args.stored if stored else ""),
         "value": T * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
@@ -112,7 +133,8 @@ def main():
                          "actor logits, written in this dtype) and report it as \"distill_grad\"")
     ap.add_argument("--stored", choices=["none", "drop", "kth", "rest"], default="none",
                     help="also time jp_obrs_forward_stored (actor side as TopK_inf ids + log-probabilities, "
-                         "only the policy tensor is swept) with this rule and report it as \"stored_actor\"")
+                         "only the policy tensor is swept) with this rule and report it as \"stored_actor\"; "
+                         "with --workload lm_head: time jp_obrs_forward_lmhead_stored instead of the two-head form")
     ap.add_argument("--token-logprob", action="store_true",
                     help="also time jp_obrs_token_logprob (log-probability of the sampled token under one "
                          "more logit tensor, one sweep) and report it as \"token_logprob\"")

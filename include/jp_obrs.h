@@ -217,6 +217,27 @@ jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Alg. 1 as a trainer runs it: the target logits lp = H_policy x W_policy come from the matrix
+ * cores one vocabulary chunk at a time (as in jp_obrs_forward_lmhead, never materialised) and the
+ * actor side is what the rollout phase stored (as in jp_obrs_forward_stored).  One head instead of
+ * two, no [T, V] tensor at all.  The target logit of a stored id is picked up when its chunk
+ * passes.  Arguments, outputs, tail rules and flags as in those two entry points; the near-tie
+ * remark of the lm_head form applies to top-k(p).
+ * Workspace: jp_obrs_lmhead_stored_workspace_bytes (one fp32 logit buffer [T, 2 chunk], one
+ * transposed weight chunk, the per-row record, plus the jp_obrs_forward workspace).
+ */
+size_t jp_obrs_lmhead_stored_workspace_bytes(int64_t T, int64_t V, int64_t d_policy, int32_t k,
+                                             int64_t vocab_chunk);
+jp_status jp_obrs_forward_lmhead_stored(const void *H_policy, int64_t d_policy, const void *W_policy,
+                                        int64_t T, int64_t V, int64_t vocab_chunk,
+                                        const int32_t *actor_topk_ids, const float *actor_topk_logprob,
+                                        const float *actor_logprob_x, const int32_t *sampled_ids,
+                                        const float *uniforms, const float *ref_logprob,
+                                        const jp_obrs_params *prm, jp_tail_rule tail_rule,
+                                        const jp_obrs_outputs *out, void *workspace,
+                                        size_t workspace_bytes, void *stream);
+
+/*
  * log-probability of the sampled token under one more logit tensor,
  *   out[t] = logits[t, x_t] - log sum_v exp(logits[t, v]),
  * e.g. log p_ref(a_t) of Alg. 1 (Phase 2, step 1) when p_ref and p_new are separate tensors: its

@@ -161,11 +161,12 @@ struct LmheadPlan {
     size_t state_stride;
 };
 
+// d_actor == 0: the stored-actor form, which has no actor head (no weight chunk, no logit buffer for it)
 bool plan_lmhead(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_t k, int64_t vocab_chunk,
                  LmheadPlan &p)
 {
     if (T < 0 || T > 0x7fffffffLL || V <= 0 || V > 0x7fffffffLL || k < 1) return false;
-    if (d_actor <= 0 || d_policy <= 0 || d_actor % 64 || d_policy % 64 || d_actor > (1 << 20) || d_policy > (1 << 20)) return false;
+    if (d_actor < 0 || d_policy <= 0 || d_actor % 64 || d_policy % 64 || d_actor > (1 << 20) || d_policy > (1 << 20)) return false;
     int64_t c = vocab_chunk > 0 ? vocab_chunk : 4096;
     c = (c + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
     const int64_t vpad = (V + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
@@ -182,7 +183,7 @@ bool plan_lmhead(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_
     p.group = p.nchunks < LM_GROUP ? p.nchunks : LM_GROUP;
     p.ldc = c * p.group;
     p.off_lp = off; off += round_up(n * (size_t)p.ldc * 4);
-    p.off_lq = off; off += round_up(n * (size_t)p.ldc * 4);
+    p.off_lq = off; off += d_actor > 0 ? round_up(n * (size_t)p.ldc * 4) : 0;
     p.bytes = off;
     return true;
 }
@@ -195,7 +196,101 @@ size_t jp_obrs_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d_actor, int
                                       int64_t vocab_chunk)
 {
     LmheadPlan p;
-    return plan_lmhead(T, V, d_actor, d_policy, k, vocab_chunk, p) ? p.bytes : 0;
+    return d_actor > 0 && plan_lmhead(T, V, d_actor, d_policy, k, vocab_chunk, p) ? p.bytes : 0;
+}
+
+size_t jp_obrs_lmhead_stored_workspace_bytes(int64_t T, int64_t V, int64_t d_policy, int32_t k, int64_t vocab_chunk)
+{
+    LmheadPlan p;
+    return plan_lmhead(T, V, 0, d_policy, k, vocab_chunk, p) ? p.bytes : 0;
+}
+
+/* Target logits from the matrix cores chunk by chunk, actor side as the rollout phase stored it. */
+jp_status jp_obrs_forward_lmhead_stored(const void *H_policy, int64_t d_policy, const void *W_policy, int64_t T,
+                                        int64_t V, int64_t vocab_chunk, const int32_t *actor_topk_ids,
+                                        const float *actor_topk_logprob, const float *actor_logprob_x,
+                                        const int32_t *sampled_ids, const float *uniforms,
+                                        const float *ref_logprob, const jp_obrs_params *prm,
+                                        jp_tail_rule tail_rule, const jp_obrs_outputs *out, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    if (!prm || !out) return JP_ERR_NULL;
+    LmheadPlan pl;
+    if (!plan_lmhead(T, V, 0, d_policy, prm->k, vocab_chunk, pl)) {
+        if (prm->k < 1) return JP_ERR_PARAM;
+        return JP_ERR_SHAPE;
+    }
+    jp_status s = check_params(prm, V, true);
+    if (s != JP_OK) return s;
+    if (prm->flags & (JP_FLAG_EXACT_Z | JP_FLAG_DISTILL_KL)) return JP_ERR_UNSUPPORTED;   // need the actor row
+    if (tail_rule != JP_TAIL_DROP && tail_rule != JP_TAIL_KTH && tail_rule != JP_TAIL_REST) return JP_ERR_PARAM;
+    if (T > 0 && (!H_policy || !W_policy || !sampled_ids || !actor_topk_ids || !actor_topk_logprob || !actor_logprob_x))
+        return JP_ERR_NULL;
+    if (!aligned16(H_policy) || ((uintptr_t)W_policy & 1)) return JP_ERR_ALIGN;
+    const bool vmajor = (prm->flags & JP_FLAG_W_VOCAB_MAJOR) != 0;
+    if (vmajor && !aligned16(W_policy)) return JP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < pl.bytes) return JP_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return JP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (T > 0) {
+        const Workspace w = carve(workspace, T);
+        char *base = (char *)workspace;
+        jp::RowArgs a{};
+        a.actor = nullptr; a.policy = base + pl.off_lp;
+        a.T = T; a.stride = pl.ldc; a.ids = sampled_ids; a.uni = uniforms;
+        a.lambda = prm->lambda; a.ln_lambda = log((double)prm->lambda); a.k = prm->k;
+        a.accept = out->accept_prob ? out->accept_prob : w.accept;
+        a.logq = out->logq ? out->logq : w.logq;
+        a.logp = out->logp ? out->logp : w.logp;
+        a.logratio = out->logratio ? out->logratio : w.logratio;
+        a.zapprox = out->z_approx ? out->z_approx : w.zapprox;
+        a.kl = w.kl;
+        a.lse_q = w.lse_q; a.lse_p = w.lse_p;
+        a.mask = out->mask ? out->mask : w.mask;
+        a.rowflag = w.rowflag;
+        a.usize = out->union_size;
+        a.topk_a = nullptr; a.topk_p = out->topk_policy;
+        a.topk_a_lq = nullptr;
+        a.topk_p_lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) ? out->topk_policy_logp : nullptr;
+        a.V_total = V; a.state = (unsigned char *)base + pl.off_state; a.state_stride = (int64_t)pl.state_stride;
+        a.stored_ids = actor_topk_ids; a.stored_logq = actor_topk_logprob; a.stored_logq_x = actor_logprob_x;
+        a.tail_rule = (int)tail_rule;
+
+        jp::GemmArgs g{};
+        g.A[0] = H_policy; g.Bt[0] = base + pl.off_wt_p; g.K[0] = (int)d_policy;
+        g.M = (int)T; g.nproblems = 1; g.ldc = pl.ldc;
+        float *const c_policy = (float *)(base + pl.off_lp);
+        int64_t group_base = 0, group_cols = 0, groups_done = 0;
+        for (int64_t j = 0; j < pl.nchunks; ++j) {
+            const int64_t v0 = j * pl.chunk;
+            const int ncols = (int)((V - v0) < pl.chunk ? (V - v0) : pl.chunk);
+            const int nthis = (ncols + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
+            g.N = nthis;
+            const int64_t slot = j % pl.group;
+            g.C[0] = c_policy + slot * pl.chunk;
+            if (slot == 0) { group_base = v0; group_cols = 0; }
+            group_cols += ncols;
+            if (!vmajor) {
+                if (jp::launch_transpose_chunk(W_policy, V, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                g.Bt[0] = base + pl.off_wt_p;
+            } else if (ncols == nthis) {
+                g.Bt[0] = (const char *)W_policy + (size_t)v0 * (size_t)d_policy * 2;
+            } else {
+                if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                g.Bt[0] = base + pl.off_wt_p;
+            }
+            if (jp::launch_gemm_pair(g, st) != hipSuccess) return JP_ERR_HIP;
+            const bool last = j + 1 == pl.nchunks;
+            if (slot + 1 == pl.group || last) {
+                a.V = group_cols; a.id_base = group_base; a.carry_in = groups_done > 0; a.carry_out = !last;
+                if (jp::launch_rows_carry_stored(a, st) != hipSuccess) return JP_ERR_HIP;
+                ++groups_done;
+            }
+        }
+    }
+    return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes, st,
+                         uniforms != nullptr);
 }
 
 jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const void *W_actor,
@@ -207,7 +302,7 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
 {
     if (!prm || !out) return JP_ERR_NULL;
     LmheadPlan pl;
-    if (!plan_lmhead(T, V, d_actor, d_policy, prm->k, vocab_chunk, pl)) {
+    if (d_actor <= 0 || !plan_lmhead(T, V, d_actor, d_policy, prm->k, vocab_chunk, pl)) {
         if (prm->k < 1) return JP_ERR_PARAM;
         return JP_ERR_SHAPE;
     }
@@ -520,6 +615,6 @@ const char *jp_status_string(jp_status s)
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 7; }
+int jp_obrs_abi_version(void) { return 8; }
 
 }  // extern "C"

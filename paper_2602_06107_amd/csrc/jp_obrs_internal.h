@@ -121,6 +121,7 @@ hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState 
 hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st);
 hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st);   // a.actor unused
+hipError_t launch_rows_carry_stored(const RowArgs &a, hipStream_t st);        // chunked fp32 policy logits + stored actor side
 hipError_t launch_distill_grad(const GradArgs &a, int dtype, int grad_dtype, hipStream_t st);
 // Two independent TN GEMMs sharing M, N and ldc (policy head and actor head of one vocabulary chunk).
 struct GemmArgs {

@@ -814,6 +814,16 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     else expand(std::integral_constant<int, 0>{});
     expand(std::integral_constant<int, 1>{});
 
+    // Chunked stored form: the target logit of a stored id is picked up by the launch whose chunk
+    // holds it and kept in the row record (in list 0's id slots, which this form never uses).
+    float *const st_slp = (float *)st_id0;
+    if constexpr (CARRY && STORED) {
+        for (int r = lane; r < k; r += WAVE) {
+            const int64_t id = (int64_t)A.stored_ids[t * k + r];
+            if (id >= id_base && id < id_base + V) st_slp[r] = ET::load1(rowp, id - id_base);
+        }
+    }
+
     if (carry_out) {                      // hand the row state to the launch of the next chunk
         if (lane == 0) {
             hdr->M2[0] = sq.M2; hdr->M2[1] = sp.M2;
@@ -867,7 +877,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
         for (int s2 = 0; s2 < SR; ++s2) {
             const int r = s2 * WAVE + lane;
             const int32_t raw_id = r < k ? A.stored_ids[t * k + r] : -1;
-            const bool ok = raw_id >= 0 && (int64_t)raw_id < V;
+            const bool ok = raw_id >= 0 && (int64_t)raw_id < V_total;
             sid[s2] = ok ? (uint32_t)raw_id : 0xffffffffu;
             slq[s2] = ok ? A.stored_logq[t * k + r] : 0.f;
             sslot[s2] = 0;
@@ -886,7 +896,9 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
             const bool keep = sid[s2] != 0xffffffffu && first[sslot[s2]] == (uint32_t)r;
             if (keep) {
                 const double dq = (double)slq[s2];
-                const double dp = (double)ET::load1(rowp, (int64_t)sid[s2]) - lse_p - ln_lambda;
+                // (the lane that wrote record entry r above is the lane that reads it here)
+                const float lp_s = CARRY ? st_slp[r] : ET::load1(rowp, (int64_t)sid[s2]);
+                const double dp = (double)lp_s - lse_p - ln_lambda;
                 zsum += (double)__builtin_amdgcn_exp2f((float)((dq < dp ? dq : dp) * LOG2E_D));
                 mass += (double)__builtin_amdgcn_exp2f((float)(dq * LOG2E_D));
                 kth = fminf(kth, slq[s2]);
@@ -898,13 +910,13 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
         mass = wave_sum(mass);
         if (n == 0) kth = 0.f;                              // nothing stored: the bound is log 1
         const double neg_inf_d = -__builtin_inf();
-        if (A.tail_rule == 0 || (int64_t)n == V) {
+        if (A.tail_rule == 0 || (int64_t)n == V_total) {
             tail_dq = neg_inf_d;
         } else if (A.tail_rule == 1) {
             tail_dq = (double)kth;
         } else {
             const double rest = mass < 1.0 ? 1.0 - mass : 0.0;
-            const double share = rest / (double)(V - n);
+            const double share = rest / (double)(V_total - n);
             tail_dq = share > 0.0 ? (double)(__builtin_amdgcn_logf((float)share)) * LN2_D : neg_inf_d;
             tail_dq = tail_dq < (double)kth ? tail_dq : (double)kth;
         }
@@ -1729,6 +1741,16 @@ hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st)
         else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, false>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, false>), grid, block, 0, st, a);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_carry_stored(const RowArgs &a, hipStream_t st)
+{
+    if (a.T <= 0) return hipSuccess;
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, false, true>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, false, true>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

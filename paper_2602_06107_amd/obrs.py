@@ -31,6 +31,7 @@ EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obr
            "jp_obrs_forward_stored", "jp_obrs_token_logprob", "jp_obrs_forward3",
            "jp_obrs_forward3_workspace_bytes", "jp_obrs_lambda_for_budget",
            "jp_obrs_lambda_for_budget_batch", "jp_obrs_budget_scratch_bytes",
+           "jp_obrs_lmhead_stored_workspace_bytes", "jp_obrs_forward_lmhead_stored",
            "jp_status_string", "jp_obrs_abi_version")
 
 
@@ -109,6 +110,13 @@ _lib.jp_obrs_lambda_for_budget_batch.restype = C.c_int
 _lib.jp_obrs_lambda_for_budget_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                                  C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
                                                  C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_lmhead_stored_workspace_bytes.restype = C.c_size_t
+_lib.jp_obrs_lmhead_stored_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int64]
+_lib.jp_obrs_forward_lmhead_stored.restype = C.c_int
+_lib.jp_obrs_forward_lmhead_stored.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_void_p, C.POINTER(Params), C.c_int, C.POINTER(Outputs),
+                                               C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.jp_status_string.restype = C.c_char_p
 _lib.jp_status_string.argtypes = [C.c_int]
 _lib.jp_obrs_abi_version.restype = C.c_int
@@ -370,6 +378,38 @@ def jp_obrs_forward_lmhead(H_actor, W_actor, H_policy, W_policy, sampled_ids, un
                                      int(vocab_chunk), _p(sampled_ids), _p(uniforms), _p(ref_logprob),
                                      C.byref(prm), C.byref(buf.out), _p(buf.workspace),
                                      buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_lmhead_stored_workspace_bytes(T, V, d_policy, k, vocab_chunk=0) -> int:
+    return int(_lib.jp_obrs_lmhead_stored_workspace_bytes(T, V, d_policy, k, vocab_chunk))
+
+
+def jp_obrs_forward_lmhead_stored(H_policy, W_policy, actor_topk_ids, actor_topk_logprob, actor_logprob_x,
+                                  sampled_ids, uniforms, ref_logprob, lam, k, c1, c2, flags, tail_rule,
+                                  buf: Buffers, vocab_chunk: int = 0, stream=None) -> None:
+    """Target logits = H_policy x W_policy on the matrix cores chunk by chunk; actor side as stored."""
+    for t in (H_policy, W_policy):
+        if t.dtype != torch.bfloat16 or t.dim() != 2 or not t.is_contiguous():
+            raise ValueError("hidden states and weights must be contiguous 2-D bfloat16 tensors")
+    T, d_p = H_policy.shape
+    if flags & JP_FLAG_W_VOCAB_MAJOR:                        # weights as [V, d]
+        V, ok = W_policy.shape[0], W_policy.shape[1] == d_p
+    else:                                                    # weights as [d, V]
+        V, ok = W_policy.shape[1], W_policy.shape[0] == d_p
+    if not ok:
+        raise ValueError("shape mismatch between hidden states and weights")
+    for t_, shape, dtype in ((actor_topk_ids, (T, k), torch.int32), (actor_topk_logprob, (T, k), torch.float32),
+                             (actor_logprob_x, (T,), torch.float32)):
+        if tuple(t_.shape) != shape or t_.dtype != dtype or not t_.is_contiguous():
+            raise ValueError("stored actor side: contiguous int32 [T, k], float32 [T, k], float32 [T]")
+    prm = Params(float(lam), int(k), float(c1), float(c2), int(flags))
+    st = _lib.jp_obrs_forward_lmhead_stored(_p(H_policy), d_p, _p(W_policy), T, V, int(vocab_chunk),
+                                            _p(actor_topk_ids), _p(actor_topk_logprob), _p(actor_logprob_x),
+                                            _p(sampled_ids), _p(uniforms), _p(ref_logprob), C.byref(prm),
+                                            int(tail_rule), C.byref(buf.out), _p(buf.workspace),
+                                            buf.workspace.numel(), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 

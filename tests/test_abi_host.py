@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert set(obrs.EXPORTS) == set(names)
-    assert obrs.jp_obrs_abi_version() == 7
+    assert obrs.jp_obrs_abi_version() == 8
 
 
 def test_struct_layouts_match_header():
@@ -183,3 +183,38 @@ def test_forward3_rejections():
     assert f(ref=None) == obrs.JP_ERR_NULL
     assert f(new=None, wsb=1 << 20) == obrs.JP_ERR_NULL       # the new policy is needed when it is the target
     assert f(tir=1, new=None) == obrs.JP_ERR_WORKSPACE        # ... and is not read when p_ref is the target
+
+
+def test_lmhead_stored_rejections_need_no_gpu():
+    """jp_obrs_forward_lmhead_stored with fake (never dereferenced) device addresses: rejected by
+    host-side validation, nothing is launched."""
+    lib = obrs.raw()
+    need = obrs.jp_obrs_lmhead_stored_workspace_bytes(4, 1024, 64, 8, 0)
+    assert need > obrs.jp_obrs_workspace_bytes(4, 1024, 8, obrs.JP_F32)
+    assert need < obrs.jp_obrs_lmhead_workspace_bytes(4, 1024, 64, 64, 8, 0)      # one head, one logit buffer
+    assert obrs.jp_obrs_lmhead_stored_workspace_bytes(4, 1024, 60, 8, 0) == 0     # d not a multiple of 64
+    assert obrs.jp_obrs_lmhead_workspace_bytes(4, 1024, 0, 64, 8, 0) == 0          # the two-head form needs both heads
+
+    def call(H=0x10000, d=64, W=0x20000, T=4, V=1024, ids=0x30000, lq=0x40000, lqx=0x50000, x=0x60000, k=8,
+             lam=1.0, flags=0, rule=1, ws=0x100000, ws_bytes=need):
+        prm = obrs.Params(lam, k, 3.0, 3.0, flags, 0, 0.0, 0.0)
+        o = obrs.Outputs()
+        return lib.jp_obrs_forward_lmhead_stored(H, d, W, T, V, 0, ids, lq, lqx, x, None, None, C.byref(prm), rule,
+                                                 C.byref(o), ws, ws_bytes, None)
+
+    assert call(H=None) == obrs.JP_ERR_NULL
+    assert call(ids=None) == obrs.JP_ERR_NULL
+    assert call(lqx=None) == obrs.JP_ERR_NULL
+    assert call(d=60) == obrs.JP_ERR_SHAPE
+    assert call(V=0) == obrs.JP_ERR_SHAPE
+    assert call(k=0) == obrs.JP_ERR_PARAM
+    assert call(k=2000) == obrs.JP_ERR_PARAM                   # k > V
+    assert call(lam=0.0) == obrs.JP_ERR_PARAM
+    assert call(rule=5) == obrs.JP_ERR_PARAM
+    assert call(flags=obrs.JP_FLAG_EXACT_Z) == obrs.JP_ERR_UNSUPPORTED
+    assert call(flags=obrs.JP_FLAG_DISTILL_KL) == obrs.JP_ERR_UNSUPPORTED
+    assert call(H=0x10008) == obrs.JP_ERR_ALIGN
+    assert call(W=0x20001) == obrs.JP_ERR_ALIGN
+    assert call(W=0x20008, flags=obrs.JP_FLAG_W_VOCAB_MAJOR) == obrs.JP_ERR_ALIGN
+    assert call(ws_bytes=need - 1) == obrs.JP_ERR_WORKSPACE
+    assert call(ws=0x100010) == obrs.JP_ERR_ALIGN
