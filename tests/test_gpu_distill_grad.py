@@ -125,6 +125,22 @@ def test_full_size_sampled_rows_and_zero_sum():
     assert torch.all(a > 0) and torch.all(a <= 2.0 + 1e-3)      # ||q - p||_1 <= 2
 
 
+def test_training_size_sampled_rows_and_zero_sum():
+    T = 65536
+    _say(f"distill grad: bf16 T={T} V=151936 (the training batch: 4.9 M workgroups), sampled rows + zero sum")
+    w = wl.training(DEV)
+    rows = [0, 1, 4095, 4096, 32767, 32768, 65534, 65535]
+    grad, _ = _check(w, torch.bfloat16, scale=1.0, rows=rows)
+    # sum_v (q - p) = 0 on every row; bf16 storage rounds each entry by <= 2^-9 of itself and
+    # sum_v |q - p| <= 2, so the row sum stays below 2 * 2^-9
+    worst = 0.0
+    for a in range(0, T, 4096):
+        worst = max(worst, grad[a:a + 4096].double().sum(dim=1).abs().max().item())
+    assert worst < 2.0 * 2.0 ** -9, worst
+    del grad, w
+    torch.cuda.empty_cache()
+
+
 def test_bad_arguments():
     _say("distill grad: host-side validation")
     w = wl.tiny(DEV)
