@@ -289,8 +289,17 @@ hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0,
 hipError_t launch_gemm_pair(const GemmArgs &g, hipStream_t st)
 {
     const int lds_bytes = NU * TILE_BYTES;      // 160 KB ring
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_tn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    // More than 64 KB of dynamic LDS has to be allowed once per device; later launches (also ones
+    // recorded into a graph) then make no call besides the launch itself.
+    static bool allowed[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !allowed[dev]) {
+        e = hipFuncSetAttribute((const void *)gemm_tn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev] = true;
+    }
     const int tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
     hipLaunchKernelGGL(gemm_tn_kernel, dim3((unsigned)tiles, 1, (unsigned)g.nproblems), dim3(GEMM_THREADS), lds_bytes, st, g);
     return hipGetLastError();

@@ -196,6 +196,43 @@ def test_vocab_major_weights_give_the_same_bits():
     assert got.stats().kappa == ref.stats().kappa
 
 
+def test_can_be_captured_in_a_hip_graph():
+    _say("lm_head + stored actor: T=48 V=3000 captured in a graph, replayed three times with eager work between")
+    w = wl.lm_head(48, 3000, 128, 192, DEV, seed=61, k=16)
+    stored = stored_side(w, w.k, np.arange(w.T))
+    d = [torch.as_tensor(a, device=DEV) for a in stored]
+    nbytes = obrs.jp_obrs_lmhead_stored_workspace_bytes(w.T, w.V, 192, w.k, 512)
+    buf = obrs.alloc_buffers(w.T, w.V, w.k, obrs.JP_F32, 0, DEV, want=WANT, workspace_bytes=nbytes)
+
+    def step():
+        obrs.jp_obrs_forward_lmhead_stored(w.H_policy, w.W_policy, d[0], d[1], d[2], w.sampled_ids, w.uniforms,
+                                           None, w.lam, w.k, w.c1, w.c2, 0, obrs.JP_TAIL_KTH, buf, 512)
+
+    step()
+    torch.cuda.synchronize()
+    ref = {n: t.clone() for n, t in buf.tensors.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                            # warm-up on the capture side
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in buf.tensors.values():
+            t.zero_()                                     # eager work between the replays
+        buf.workspace.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in ref:
+            same = torch.equal(buf.tensors[n], ref[n]) or (
+                ref[n].is_floating_point() and torch.equal(torch.nan_to_num(buf.tensors[n]), torch.nan_to_num(ref[n])))
+            assert same, (rep, n)
+
+
 def test_rejected_arguments():
     _say("lm_head + stored actor: host-side validation")
     w = wl.lm_head(8, 512, 64, 64, DEV, seed=3, k=4)
