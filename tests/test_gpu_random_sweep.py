@@ -11,6 +11,7 @@ if torch.cuda.is_available():
     from paper_2602_06107_amd import obrs
     from paper_2602_06107_amd import workloads as wl
     import parity_util as pu
+    import test_gpu_stored as stored_form
 
 DEV = "cuda"
 ALL_FLAGS = 1 | 2 | 8
@@ -32,10 +33,7 @@ def _case(seed):
     return dict(seed=seed, dtype=dtype, V=V, T=T, k=k, lam=lam, stride=stride, quant=quant, mask_frac=mask_frac)
 
 
-@pytest.mark.parametrize("seed", range(40))
-def test_random_case(seed):
-    c = _case(seed)
-    print({n: (str(v) if n == "dtype" else v) for n, v in c.items()}, flush=True)
+def _workload(c, seed):
     w = wl.make_logits(c["T"], c["V"], c["dtype"], seed=5000 + seed, device=DEV, actor_sigma=2.0,
                        spikes=min(3, c["V"]), noise_sigma=0.8, pad_every=6, row_stride=c["stride"])
     w = w.with_params(lam=c["lam"], k=c["k"])
@@ -55,4 +53,21 @@ def test_random_case(seed):
         drop2[:, 0] = False
         w.policy[:, : c["V"]][drop2] = float("-inf")
     w.ref_logprob = -torch.rand(c["T"], generator=g, device=DEV) * 3.0
-    pu.check_all(w, ALL_FLAGS)
+    return w
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_case(seed):
+    c = _case(seed)
+    print({n: (str(v) if n == "dtype" else v) for n, v in c.items()}, flush=True)
+    pu.check_all(_workload(c, seed), ALL_FLAGS)
+
+
+@pytest.mark.parametrize("seed", range(40, 64))
+def test_random_case_stored_actor_side(seed):
+    """The same kind of case through jp_obrs_forward_stored, the stored side taken from the actor row
+    (its top-k by (value desc, id asc), in float64 on the host), one of the three tail rules."""
+    c = _case(seed)
+    rule = seed % 3
+    print({n: (str(v) if n == "dtype" else v) for n, v in c.items()}, "rule", rule, flush=True)
+    stored_form.run_case(_workload(c, seed), rule, flags=2)
