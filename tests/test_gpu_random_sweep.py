@@ -12,6 +12,7 @@ if torch.cuda.is_available():
     from paper_2602_06107_amd import workloads as wl
     import parity_util as pu
     import test_gpu_stored as stored_form
+    import test_gpu_budget as budget
 
 DEV = "cuda"
 ALL_FLAGS = 1 | 2 | 8
@@ -71,3 +72,17 @@ def test_random_case_stored_actor_side(seed):
     rule = seed % 3
     print({n: (str(v) if n == "dtype" else v) for n, v in c.items()}, "rule", rule, flush=True)
     stored_form.run_case(_workload(c, seed), rule, flags=2)
+
+
+@pytest.mark.parametrize("seed", range(64, 88))
+def test_random_case_budget(seed):
+    """The same kind of case through jp_obrs_lambda_for_budget with a random budget per row, and
+    through the per-batch solver with one random budget."""
+    c = _case(seed)
+    print({n: (str(v) if n == "dtype" else v) for n, v in c.items()}, flush=True)
+    w = _workload(c, seed)
+    rng = np.random.default_rng(seed)
+    targets = rng.choice([1.0, 0.999, 0.9, 0.5, 0.2, 0.01], size=c["T"]).astype(np.float32)
+    budget._check(w, 0.5, row_target=targets)
+    if bool((w.sampled_ids >= 0).any()):
+        budget._check_batch(w, float(rng.choice([0.9, 0.5, 0.1])))
