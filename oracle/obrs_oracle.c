@@ -148,13 +148,19 @@ static void accept_and_mask(jpo_row_out *out, double u, double lambda)
 
 /* ---- one token position ------------------------------------------------
  * lq, lp: logits of the rollout and the target model over V tokens.
- * x: sampled token (x < 0 marks a padding row), u: uniform in [0,1).
+ * x: sampled token (x < 0 marks a padding row; x >= V is no token of the vocabulary: the row is
+ * left out like a padding row, with NaN results), u: uniform in [0,1).
  * topk_q / topk_p (each k ids) may be NULL.                              */
 void jpo_row(const double *lq, const double *lp, int64_t V, int32_t x, double u,
              double lambda, int32_t k, jpo_row_out *out, int32_t *topk_q, int32_t *topk_p)
 {
     memset(out, 0, sizeof *out);
     if (x < 0) return;
+    if ((int64_t)x >= V) {                  /* not a token of this vocabulary: no part of the batch */
+        out->lse_q = out->lse_p = out->logq_x = out->logp_x = out->logratio = out->accept = NAN;
+        out->z_approx = out->z_exact = out->kl_p_q = out->kl_p_qtilde = NAN;
+        return;
+    }
     out->valid = 1;
 
     double lse_q = jpo_logsumexp(lq, V);
@@ -233,6 +239,11 @@ void jpo_row_stored(const double *lp, int64_t V, const int32_t *ids_q, const dou
 {
     memset(out, 0, sizeof *out);
     if (x < 0) return;
+    if ((int64_t)x >= V) {                  /* not a token of this vocabulary: no part of the batch */
+        out->lse_q = out->lse_p = out->logq_x = out->logp_x = out->logratio = out->accept = NAN;
+        out->z_approx = out->z_exact = out->kl_p_q = out->kl_p_qtilde = NAN;
+        return;
+    }
     out->valid = 1;
     double lse_p = jpo_logsumexp(lp, V);
     out->lse_q = 0.0;
@@ -419,12 +430,6 @@ void jpo_distill_grad(const void *actor, const void *policy, int dtype, int64_t 
     free(lq);
 }
 
-/* ---- batch-level bias correction and weights (Sec. 4.4.2, Alg. 1 step 2-3)
- * mask[t] is taken as given (the Bernoulli draw is an input of this stage).
- * alpha_hat = accepted / proposed;  kappa = alpha_hat / mean(Z_approx);
- * Z_t = kappa Z_approx;  w = Z_t max(lambda, p(x)/q(x));
- * rho = min(w, c1) * min(p_ref(x)/p(x), c2)   (second factor 1 if no ref).
- * use_expected_alpha != 0 replaces alpha_hat by the mean of a(x).        */
 /* ---- the scaling factor for a given acceptance budget (Sec. 3.3, Theorem 2) -----------------
  * For a budget abar in (0, 1] there is a lambda with sum_v q_v min(1, p_v / (lambda q_v)) = abar.
  * The left side is Z(lambda) = sum_{r_v > lambda} q_v + (1/lambda) sum_{r_v <= lambda} p_v with
@@ -552,6 +557,12 @@ double jpo_adjust(double w, int f_mode, double c1, double lo, double hi)
     return w < c1 ? w : c1;
 }
 
+/* ---- batch-level bias correction and weights (Sec. 4.4.2, Alg. 1 step 2-3)
+ * mask[t] is taken as given (the Bernoulli draw is an input of this stage).
+ * alpha_hat = accepted / proposed;  kappa = alpha_hat / mean(Z_approx);
+ * Z_t = kappa Z_approx;  w = Z_t max(lambda, p(x)/q(x));
+ * rho = F(w) * min(p_ref(x)/p(x), c2)   (second factor 1 if no ref; F by f_mode).
+ * use_expected_alpha != 0 replaces alpha_hat by the mean of a(x).        */
 void jpo_batch_f(const jpo_row_out *rows, const int32_t *mask, int64_t T, double lambda,
                  int f_mode, double c1, double f_lo, double f_hi, double c2,
                  const double *ref_logprob, int use_expected_alpha,

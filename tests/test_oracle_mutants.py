@@ -71,6 +71,9 @@ MUTANTS = [
      "out[v] = weight * (exp(lq[v] - lse_q) - exp(lp[v] - lse_p));", "out[v] = weight * (exp(lp[v] - lse_p) - exp(lq[v] - lse_q));"),
     ("distillation gradient drops the row weight",
      "jpo_distill_grad_row(lq, lp, V, scale * (row_scale ? (double)row_scale[t] : 1.0), o);", "jpo_distill_grad_row(lq, lp, V, scale, o);"),
+    ("a sampled id outside the vocabulary is taken as a padding row with zero results",
+     "out->z_approx = out->z_exact = out->kl_p_q = out->kl_p_qtilde = NAN;\n        return;\n    }\n    out->valid = 1;\n\n",
+     "return;\n    }\n    out->valid = 1;\n\n"),
     ("distillation gradient fills padding rows",
      "if (x[t] < 0 || x[t] >= V || !isfinite(lse_q) || !isfinite(lse_p)) {", "if (x[t] >= V || !isfinite(lse_q) || !isfinite(lse_p)) {"),
 ]
@@ -99,3 +102,64 @@ def test_pins_catch_planted_mistake(tmp_path, name, old, new):
                         "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert r.returncode != 0, f"no pin caught: {name}"
     assert "failed" in r.stdout, r.stdout[-500:]
+
+
+# ---- the Python part of the oracle (the fused lm_head form's logits) -------------------------------
+PY_SRC = os.path.join(ROOT, "oracle", "obrs_oracle.py")
+
+PY_MUTANTS = [
+    ("lm_head logits: bf16 bits widened by the wrong shift",
+     "(a.astype(np.uint32) << 16)", "(a.astype(np.uint32) << 15)"),
+    ("lm_head logits: bf16 bits taken as integers",
+     "return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)", "return a.astype(np.float64)"),
+    ("lm_head logits: the projection is used transposed",
+     "return wide(H) @ wide(W)", "return wide(H) @ wide(W).T"),
+    ("lm_head logits: the product is taken in float32",
+     "return wide(H) @ wide(W)", "return (wide(H).astype(np.float32) @ wide(W).astype(np.float32)).astype(np.float64)"),
+]
+
+_RUNNER = """
+import importlib.util, sys
+sys.path.insert(0, {root!r})
+import oracle
+spec = importlib.util.spec_from_file_location("oracle.obrs_oracle", {mutant!r})
+m = importlib.util.module_from_spec(spec)
+sys.modules["oracle.obrs_oracle"] = m
+spec.loader.exec_module(m)
+oracle.obrs_oracle = m
+import pytest
+sys.exit(pytest.main([{pins!r}, "-x", "-q", "-p", "no:cacheprovider", "-k", "lm_head"]))
+"""
+
+
+def test_python_mutant_snippets_exist_in_the_oracle():
+    src = open(PY_SRC).read()
+    for name, old, _ in PY_MUTANTS:
+        assert src.count(old) == 1, name
+
+
+@pytest.mark.parametrize("name,old,new", PY_MUTANTS,
+                         ids=[m[0] for m in PY_MUTANTS])
+def test_pins_catch_planted_mistake_in_the_python_part(tmp_path, name, old, new):
+    from oracle import obrs_oracle as real
+    mutant = tmp_path / "obrs_oracle_mutant.py"
+    mutant.write_text(open(PY_SRC).read().replace(old, new))
+    # the mutant module sits outside the oracle folder: point it at the built C library
+    env = dict(os.environ, JPO_ORACLE_LIB=real.build())
+    pins = os.path.join(ROOT, "tests", "test_oracle_pins.py")
+    r = subprocess.run([sys.executable, "-c", _RUNNER.format(root=ROOT, mutant=str(mutant), pins=pins)],
+                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"no pin caught: {name}"
+    assert "failed" in r.stdout, r.stdout[-500:]
+
+
+def test_unmutated_python_part_passes_through_the_same_runner(tmp_path):
+    """The runner itself must not be what fails: the unchanged source passes the same pins."""
+    from oracle import obrs_oracle as real
+    copy = tmp_path / "obrs_oracle_copy.py"
+    copy.write_text(open(PY_SRC).read())
+    env = dict(os.environ, JPO_ORACLE_LIB=real.build())
+    pins = os.path.join(ROOT, "tests", "test_oracle_pins.py")
+    r = subprocess.run([sys.executable, "-c", _RUNNER.format(root=ROOT, mutant=str(copy), pins=pins)],
+                       env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-800:]

@@ -738,3 +738,74 @@ def test_lambda_for_budget_batch_against_bisection_on_the_mean():
     assert orc.lambda_for_budget_batch(a, p, x1, 0.4) == pytest.approx(orc.lambda_for_budget(a[4], p[4], 0.4), rel=1e-13)
     assert math.isnan(orc.lambda_for_budget_batch(a, p, np.full(T, -1, np.int32), 0.5))
     assert math.isnan(orc.lambda_for_budget_batch(a, p, x, 0.0))
+
+
+# ---- logits of the fused lm_head form: exact products of the stored bf16 values ------------------
+# (not an operation of the paper; the workload defines the logits as hidden states [n, d] times the
+# vocabulary projection [d, V], both bf16, with nothing rounded before the OBRS computation)
+
+def _bf16_as_fraction(bits):
+    """The value of one bfloat16 bit pattern as an exact rational: 1 sign, 8 exponent, 7 fraction bits."""
+    from fractions import Fraction
+    sign = -1 if (bits >> 15) & 1 else 1
+    e = (bits >> 7) & 0xff
+    m = bits & 0x7f
+    assert e != 0xff
+    if e == 0:
+        return sign * Fraction(m, 1 << 7) * Fraction(1, 1 << 126)
+    two_e = Fraction(1 << (e - 127)) if e >= 127 else Fraction(1, 1 << (127 - e))
+    return sign * Fraction((1 << 7) | m, 1 << 7) * two_e
+
+
+def _bf16_bits(rng, shape, e_lo=121, e_hi=131):
+    """Random bf16 bit patterns with biased exponents in [e_lo, e_hi] (values between 2^-6 and 2^5)."""
+    s = rng.integers(0, 2, shape).astype(np.uint16)
+    e = rng.integers(e_lo, e_hi + 1, shape).astype(np.uint16)
+    m = rng.integers(0, 128, shape).astype(np.uint16)
+    return (s << 15) | (e << 7) | m
+
+
+@pytest.mark.parametrize("n,d,V", [(3, 5, 7), (4, 4, 4), (1, 9, 2), (2, 1, 6)])
+def test_lm_head_logits_are_the_exact_products_of_the_bf16_values(n, d, V):
+    rng = np.random.default_rng(500 + 31 * n + 7 * d + V)
+    H, W = _bf16_bits(rng, (n, d)), _bf16_bits(rng, (d, V))
+    H[0, 0] = 0x0000                     # +0
+    W[-1, -1] = 0x8000                   # -0
+    if d > 1:
+        H[-1, 1] = 0x3f80                # 1.0
+        W[1, 0] = 0xc000                 # -2.0
+    got = orc.lm_head_logits(H, W)
+    assert got.shape == (n, V) and got.dtype == np.float64
+    for i in range(n):
+        for v in range(V):
+            exact = sum(_bf16_as_fraction(int(H[i, j])) * _bf16_as_fraction(int(W[j, v])) for j in range(d))
+            # 16-bit products with exponents 22 apart at most: every partial sum is exact in float64
+            assert got[i, v] == float(exact), (i, v)
+            assert float(exact) == exact
+
+
+def test_lm_head_logits_known_values_and_float_inputs():
+    # H = [[1, 2, 0.5]], W rows (1, -1), (0.25, 3), (-4, 8): logits (1 + 0.5 - 2, -1 + 6 + 4) = (-0.5, 9)
+    H = np.array([[0x3f80, 0x4000, 0x3f00]], dtype=np.uint16)
+    W = np.array([[0x3f80, 0xbf80], [0x3e80, 0x4040], [0xc080, 0x4100]], dtype=np.uint16)
+    np.testing.assert_array_equal(orc.lm_head_logits(H, W), [[-0.5, 9.0]])
+    # the same through float inputs (values taken as they are)
+    Hf = np.array([[1.0, 2.0, 0.5]], dtype=np.float32)
+    Wf = np.array([[1.0, -1.0], [0.25, 3.0], [-4.0, 8.0]])
+    np.testing.assert_array_equal(orc.lm_head_logits(Hf, Wf), [[-0.5, 9.0]])
+    # a bit pattern is not its integer value: 0x3f80 is 1.0, not 16256
+    assert orc.lm_head_logits(np.array([[0x3f80]], dtype=np.uint16), np.array([[0x3f80]], dtype=np.uint16))[0, 0] == 1.0
+
+
+def test_row_with_a_sampled_id_outside_the_vocabulary_is_left_out():
+    rng = np.random.default_rng(77)
+    V = 12
+    lq, lp = _rand_logits(rng, V), _rand_logits(rng, V)
+    bad, _, _ = orc.row(lq, lp, V, 0.3, 1.0, 3)
+    assert bad.valid == 0 and math.isnan(bad.accept) and math.isnan(bad.z_approx)
+    good, kq, _ = orc.row(lq, lp, V - 1, 0.3, 1.0, 3)
+    assert good.valid == 1
+    b, w, rho = orc.batch(_rows_from([good, bad]), [good.mask, 0], 1.0, 3.0, 3.0)
+    assert b.n_valid == 1 and b.mean_z_approx == good.z_approx and w[1] == 0.0 and rho[1] == 0.0
+    sb, _ = orc.row_stored(lp, kq, lq[kq] - scipy.special.logsumexp(lq), -1.0, V + 5, 0.3, 1.0, 3, 1)
+    assert sb.valid == 0 and math.isnan(sb.z_approx)
