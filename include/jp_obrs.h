@@ -30,7 +30,11 @@
  *   - Errors the host can see return a status before anything is launched.  Errors only the
  *     device can see (sampled id >= V, non-finite log-sum-exp, no valid row) set bits in
  *     jp_obrs_stats.error_flags and put NaN in the affected outputs.
- *   - Re-entrant; no global state.  Calls that share a workspace must be ordered by the caller.
+ *   - Re-entrant.  Calls that share a workspace must be ordered by the caller.  The library keeps
+ *     two pieces of process-wide state, both written once per device through atomics: whether the
+ *     GEMM kernel of the lm_head forms has been allowed its 160 KB of LDS on that device (one
+ *     hipFuncSetAttribute on the first lm_head call there, which therefore must not run under
+ *     stream capture), and the address of the static scratch of jp_obrs_forward_static.
  */
 #ifndef JP_OBRS_H
 #define JP_OBRS_H
@@ -43,6 +47,7 @@ extern "C" {
 #endif
 
 #define JP_K_MAX 256            /* largest supported top-k count per distribution */
+#define JP_STATIC_MAX_T 131072  /* most token positions jp_obrs_forward_static takes     */
 
 typedef enum jp_status {
     JP_OK = 0,
@@ -52,7 +57,8 @@ typedef enum jp_status {
     JP_ERR_ALIGN = 4,           /* pointer or row pitch not 16-byte aligned            */
     JP_ERR_WORKSPACE = 5,       /* workspace NULL or smaller than jp_obrs_workspace_bytes */
     JP_ERR_UNSUPPORTED = 6,     /* k > JP_K_MAX, unknown dtype or flag                 */
-    JP_ERR_HIP = 7              /* a HIP launch failed                                 */
+    JP_ERR_HIP = 7,             /* a HIP launch failed                                 */
+    JP_ERR_TOO_LARGE = 8        /* jp_obrs_forward_static only: T > JP_STATIC_MAX_T    */
 } jp_status;
 
 typedef enum jp_dtype { JP_F32 = 0, JP_BF16 = 1 } jp_dtype;
@@ -141,6 +147,30 @@ jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits,
                           const jp_obrs_params *prm, const jp_obrs_outputs *out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * jp_obrs_forward for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * scratch that jp_obrs_forward takes as `workspace` (the per-token scalars kept between the row
+ * stage and the batch stage, ~46 bytes per token) is here a static device array inside the library,
+ * sized for T <= JP_STATIC_MAX_T (5.75 MiB; every GPU the library runs on holds it until the process
+ * ends).  Same kernels, same results bit for bit; no hipMalloc, hipFree or allocating library call.
+ *   - T > JP_STATIC_MAX_T returns JP_ERR_TOO_LARGE and launches nothing.
+ *   - The GPU whose stream is passed must be the current device of the calling thread.  The first
+ *     call on a device looks the array's address up (hipGetSymbolAddress) and must be made outside
+ *     stream capture; later calls only launch.
+ *   - All calls on one GPU share the one array: calls whose enqueued work may overlap in time (two
+ *     streams, two threads) race on it and must be ordered by the caller; jp_obrs_forward with
+ *     separate workspaces has no such limit.  Nothing in the array needs clearing between calls:
+ *     the row stage writes every entry of the first T positions before the batch stage reads them,
+ *     whatever an earlier, larger call left behind.
+ * Inputs, outputs and every other convention as jp_obrs_forward.
+ */
+jp_status jp_obrs_forward_static(const void *actor_logits, const void *policy_logits,
+                                 int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
+                                 const int32_t *sampled_ids, const float *uniforms,
+                                 const float *ref_logprob, const jp_obrs_params *prm,
+                                 const jp_obrs_outputs *out, void *stream);
+
 /* Row stage only (everything of jp_obrs_forward that needs no batch statistic). */
 jp_status jp_obrs_rows(const void *actor_logits, const void *policy_logits,
                        int64_t T, int64_t V, int64_t row_stride, jp_dtype dt,
@@ -151,6 +181,9 @@ jp_status jp_obrs_rows(const void *actor_logits, const void *policy_logits,
 /*
  * Batch stage only (Sec. 4.4.2 and Alg. 1 step 3) over the per-row results that a preceding
  * jp_obrs_rows call with the SAME workspace, T and outputs struct left behind.
+ * This call cannot see whether the row stage was given uniforms: if it ran with uniforms == NULL
+ * (no Bernoulli draw, every mask 0), set JP_FLAG_ALPHA_EXPECTED here, otherwise alpha_hat and with
+ * it kappa, w_t and rho_t come out 0.
  */
 jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *ref_logprob,
                            const jp_obrs_params *prm, const jp_obrs_outputs *out,

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "jp_obrs_internal.h"
@@ -290,15 +291,17 @@ hipError_t launch_gemm_pair(const GemmArgs &g, hipStream_t st)
 {
     const int lds_bytes = NU * TILE_BYTES;      // 160 KB ring
     // More than 64 KB of dynamic LDS has to be allowed once per device; later launches (also ones
-    // recorded into a graph) then make no call besides the launch itself.
-    static bool allowed[64];
+    // recorded into a graph) then make no call besides the launch itself.  The flag is only ever set,
+    // through an atomic, after the attribute call has succeeded; two threads racing on a device's
+    // first call both make that (idempotent) call.
+    static std::atomic<bool> allowed[64];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64 || !allowed[dev]) {
+    if (dev < 0 || dev >= 64 || !allowed[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute((const void *)gemm_tn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 64) allowed[dev] = true;
+        if (dev >= 0 && dev < 64) allowed[dev].store(true, std::memory_order_release);
     }
     const int tiles = ((g.M + BM - 1) / BM) * (g.N / BN);
     hipLaunchKernelGGL(gemm_tn_kernel, dim3((unsigned)tiles, 1, (unsigned)g.nproblems), dim3(GEMM_THREADS), lds_bytes, st, g);

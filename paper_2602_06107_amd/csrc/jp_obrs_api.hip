@@ -2,6 +2,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "jp_obrs_internal.h"
 
 namespace {
@@ -46,6 +48,35 @@ Workspace carve(void *base, int64_t T)
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// ---- static scratch of the entry point that allocates nothing ------------------------------------
+// The same layout carve() gives a caller's workspace, for up to JP_STATIC_MAX_T token positions, in
+// a device array that every GPU the library runs on holds until the process ends (5.75 MiB).
+constexpr size_t round_up_c(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+constexpr size_t static_scratch_bytes(size_t n)
+{
+    return 7 * round_up_c(n * 4) + 2 * round_up_c(n * 8) + 2 * round_up_c(n) + round_up_c(sizeof(jp_obrs_stats));
+}
+constexpr size_t STATIC_SCRATCH_BYTES = static_scratch_bytes(JP_STATIC_MAX_T);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle; every GPU
+// holds its own copy at its own address).  Looked up once per device, with that device current.
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> scratch_ptr[MAX_DEVICES];
+
+jp_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return JP_ERR_HIP;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return JP_ERR_HIP;
+        scratch_ptr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+    }
+    *ptr = p;
+    return JP_OK;
+}
 
 jp_status check_params(const jp_obrs_params *prm, int64_t V, bool need_clips)
 {
@@ -424,6 +455,30 @@ jp_status jp_obrs_forward(const void *actor_logits, const void *policy_logits, i
                          (hipStream_t)stream, uniforms != nullptr);
 }
 
+/* jp_obrs_forward on the library's static scratch instead of a caller's workspace. */
+jp_status jp_obrs_forward_static(const void *actor_logits, const void *policy_logits, int64_t T, int64_t V,
+                                 int64_t row_stride, jp_dtype dt, const int32_t *sampled_ids,
+                                 const float *uniforms, const float *ref_logprob, const jp_obrs_params *prm,
+                                 const jp_obrs_outputs *out, void *stream)
+{
+    if (T > JP_STATIC_MAX_T) return JP_ERR_TOO_LARGE;       // before anything touches the GPU
+    if (T < 0) return JP_ERR_SHAPE;
+    if (carve(nullptr, T).bytes > STATIC_SCRATCH_BYTES) return JP_ERR_TOO_LARGE;
+    if (!prm || !out) return JP_ERR_NULL;
+    // every argument error is reported before the scratch is looked up (which needs a GPU)
+    jp_status s = check_shape(T, V, row_stride, dt);
+    if (s == JP_OK) s = check_params(prm, V, true);
+    if (s != JP_OK) return s;
+    if (T > 0 && (!actor_logits || !policy_logits || !sampled_ids)) return JP_ERR_NULL;
+    const size_t esz = dt == JP_BF16 ? 2 : 4;
+    if (!aligned16(actor_logits) || !aligned16(policy_logits) || ((size_t)row_stride * esz) % 16 != 0) return JP_ERR_ALIGN;
+    void *ws = nullptr;
+    s = static_scratch(&ws);
+    if (s != JP_OK) return s;
+    return jp_obrs_forward(actor_logits, policy_logits, T, V, row_stride, dt, sampled_ids, uniforms, ref_logprob,
+                           prm, out, ws, STATIC_SCRATCH_BYTES, stream);
+}
+
 /* Whole hot path with the actor side as the rollout phase stored it (ids + log-probabilities). */
 jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V, int64_t row_stride,
                                  jp_dtype dt, const int32_t *actor_topk_ids, const float *actor_topk_logprob,
@@ -611,10 +666,11 @@ const char *jp_status_string(jp_status s)
     case JP_ERR_WORKSPACE: return "workspace missing or too small";
     case JP_ERR_UNSUPPORTED: return "unsupported dtype, flag or k";
     case JP_ERR_HIP: return "HIP launch failed";
+    case JP_ERR_TOO_LARGE: return "more token positions than the static scratch of the no-allocation entry point holds";
     }
     return "unknown status";
 }
 
-int jp_obrs_abi_version(void) { return 8; }
+int jp_obrs_abi_version(void) { return 9; }
 
 }  // extern "C"

@@ -24,7 +24,8 @@ JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
 JP_TAIL_DROP, JP_TAIL_KTH, JP_TAIL_REST = 0, 1, 2
 JP_F_TRUNCATE, JP_F_IDENTITY, JP_F_BAND = 0, 1, 2
 (JP_OK, JP_ERR_NULL, JP_ERR_SHAPE, JP_ERR_PARAM, JP_ERR_ALIGN, JP_ERR_WORKSPACE,
- JP_ERR_UNSUPPORTED, JP_ERR_HIP) = range(8)
+ JP_ERR_UNSUPPORTED, JP_ERR_HIP, JP_ERR_TOO_LARGE) = range(9)
+JP_STATIC_MAX_T = 131072
 
 EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obrs_finalize",
            "jp_obrs_lmhead_workspace_bytes", "jp_obrs_forward_lmhead", "jp_obrs_distill_grad",
@@ -32,7 +33,7 @@ EXPORTS = ("jp_obrs_workspace_bytes", "jp_obrs_forward", "jp_obrs_rows", "jp_obr
            "jp_obrs_forward3_workspace_bytes", "jp_obrs_lambda_for_budget",
            "jp_obrs_lambda_for_budget_batch", "jp_obrs_budget_scratch_bytes",
            "jp_obrs_lmhead_stored_workspace_bytes", "jp_obrs_forward_lmhead_stored",
-           "jp_status_string", "jp_obrs_abi_version")
+           "jp_obrs_forward_static", "jp_status_string", "jp_obrs_abi_version")
 
 
 class Params(C.Structure):
@@ -68,6 +69,10 @@ _lib.jp_obrs_forward.restype = C.c_int
 _lib.jp_obrs_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params),
                                  C.POINTER(Outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.jp_obrs_forward_static.restype = C.c_int
+_lib.jp_obrs_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Params),
+                                        C.POINTER(Outputs), C.c_void_p]
 _lib.jp_obrs_rows.restype = C.c_int
 _lib.jp_obrs_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                               C.c_void_p, C.c_void_p, C.POINTER(Params), C.POINTER(Outputs),
@@ -236,6 +241,17 @@ def jp_obrs_forward(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c
     st = _lib.jp_obrs_forward(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
                               _p(ref_logprob), C.byref(prm), C.byref(buf.out), _p(buf.workspace),
                               buf.workspace.numel(), _stream_handle(stream))
+    if st != JP_OK:
+        raise JpError(st)
+
+
+def jp_obrs_forward_static(actor, policy, sampled_ids, uniforms, ref_logprob, lam, k, c1, c2, flags,
+                           buf: Buffers, stream=None, adjust=None) -> None:
+    """jp_obrs_forward on the library's static scratch: ``buf.workspace`` is not used or passed."""
+    T, V, stride, dt = _logit_args(actor, policy)
+    prm = _params(lam, k, c1, c2, flags, adjust)
+    st = _lib.jp_obrs_forward_static(_p(actor), _p(policy), T, V, stride, dt, _p(sampled_ids), _p(uniforms),
+                                     _p(ref_logprob), C.byref(prm), C.byref(buf.out), _stream_handle(stream))
     if st != JP_OK:
         raise JpError(st)
 

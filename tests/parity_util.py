@@ -40,14 +40,21 @@ def _close(got, want, rel, what, abs_tol=0.0):
                            f"want {want.flat[np.argmax(err - bound)]!r}")
 
 
-def check_rows(buf, w, R, rows=None, flags=0, tol=None, stored=False):
+def host_outputs(buf):
+    """Every output tensor of a call copied to the host once (for checks that go through the batch in pieces)."""
+    return {n: t.cpu().numpy() for n, t in buf.tensors.items() if n != "stats"}
+
+
+def check_rows(buf, w, R, rows=None, flags=0, tol=None, stored=False, host=None):
     """Per-row outputs of the HIP path against oracle rows R (for all rows or the sampled ones).
-    stored=True: the stored-actor form, where the actor list is an input and is not written."""
+    stored=True: the stored-actor form, where the actor list is an input and is not written.
+    host: the outputs as host_outputs(buf) returned them (else they are copied here)."""
     tol = TOL[w.actor.dtype] if tol is None else tol
     idx = np.arange(w.T) if rows is None else np.asarray(rows)
     o = R.out
     valid = o["valid"] == 1
-    g = {n: t.cpu().numpy()[idx] for n, t in buf.tensors.items() if n != "stats"}
+    host = host_outputs(buf) if host is None else host
+    g = {n: a[idx] for n, a in host.items()}
 
     # padding rows: zeros, ids -1
     if (~valid).any():

@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert set(obrs.EXPORTS) == set(names)
-    assert obrs.jp_obrs_abi_version() == 8
+    assert obrs.jp_obrs_abi_version() == 9
 
 
 def test_struct_layouts_match_header():
@@ -42,6 +42,9 @@ def test_workspace_bytes():
     assert f(8192, 151936, 64, obrs.JP_BF16) >= 8192 * (7 * 4 + 2 * 8 + 2)
     assert f(8192, 151936, 64, obrs.JP_BF16) < 8192 * 64
     assert f(-1, 10, 1, obrs.JP_F32) == 0 and f(4, 0, 1, obrs.JP_F32) == 0 and f(4, 10, 1, 7) == 0
+
+
+A0, P0, X0 = 0x10000, 0x20000, 0x30000
 
 
 def _call(actor=0x10000, policy=0x20000, T=4, V=1024, stride=1024, dt=None, ids=0x30000, uni=0x40000,
@@ -92,9 +95,37 @@ def test_invalid_arguments_are_rejected_before_launch(kw, want):
     assert _call(**kw) == want
 
 
+def _call_static(actor=A0, policy=P0, T=4, V=1024, stride=1024, dt=0, ids=X0, lam=1.0, k=8, prm_null=False):
+    lib = obrs.raw()
+    prm = obrs.Params(lam, k, 3.0, 3.0, 0, 0, 0.0, 0.0)
+    o = obrs.Outputs()
+    return lib.jp_obrs_forward_static(actor, policy, T, V, stride, dt, ids, None, None,
+                                      None if prm_null else C.byref(prm), C.byref(o), None)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(T=obrs.JP_STATIC_MAX_T + 1), obrs.JP_ERR_TOO_LARGE),      # beyond the static scratch: a status of its own
+    (dict(T=1 << 40), obrs.JP_ERR_TOO_LARGE),
+    (dict(T=-1), obrs.JP_ERR_SHAPE),
+    (dict(prm_null=True), obrs.JP_ERR_NULL),
+    (dict(actor=None), obrs.JP_ERR_NULL),
+    (dict(V=0), obrs.JP_ERR_SHAPE),
+    (dict(k=0), obrs.JP_ERR_PARAM),
+    (dict(k=257), obrs.JP_ERR_UNSUPPORTED),
+    (dict(lam=0.0), obrs.JP_ERR_PARAM),
+    (dict(policy=0x20008), obrs.JP_ERR_ALIGN),
+    (dict(dt=1, V=1020, stride=1020), obrs.JP_ERR_ALIGN),
+])
+def test_static_scratch_entry_point_rejects_before_touching_the_gpu(kw, want):
+    """Every argument error of jp_obrs_forward_static comes back before its scratch is looked up,
+    so these calls work (and launch nothing) on a machine without a GPU."""
+    assert _call_static(**kw) == want
+    assert "static scratch" in obrs.jp_status_string(obrs.JP_ERR_TOO_LARGE)
+
+
 def test_status_strings():
     seen = set()
-    for s in range(8):
+    for s in range(9):
         msg = obrs.jp_status_string(s)
         assert msg and msg not in seen
         seen.add(msg)

@@ -4,7 +4,10 @@ one vocabulary chunk at a time; the oracle forms them in float64 from the same b
 Because the two sides round the logits differently (~1e-5), a top-k list may differ from the
 oracle's where two logits are nearly tied: an id list is accepted if, rank by rank, the float64
 logit of the GPU's id is within 1e-4 max(1, |l|) of the oracle's; Z_approx is then compared on the
-set the GPU chose.  Floats: the bf16-input bar (rel 1e-3, absolute for log-domain values)."""
+set the GPU chose.  Floats: the bf16-input bar (rel 1e-3, absolute for log-domain values).  The
+Bernoulli draw: a logit accumulated in fp32 over d products carries ~1e-5 of rounding, so a(x)
+differs from the oracle's by a few 1e-5 relative and a uniform within 1e-4 a of it may fall on
+either side (the materialised path's band is 1e-5 because its logits are exact inputs)."""
 import numpy as np
 import pytest
 import torch
@@ -20,6 +23,7 @@ if torch.cuda.is_available():
 DEV = "cuda"
 TOL = 1e-3
 TIE = 1e-4
+MASK_BAND = 1e-4
 
 
 def _run(w, flags=0, vocab_chunk=0):
@@ -68,7 +72,7 @@ def _check(w, buf, rows, flags=0, batch=True):
         if flags & obrs.JP_FLAG_TOPK_LOGPROBS:
             pu._close(g["topk_actor_logq"][i], logq[g["topk_actor"][i]], 0.0, "top-k log q", abs_tol=TOL)
             pu._close(g["topk_policy_logp"][i], logp[g["topk_policy"][i]], 0.0, "top-k log p", abs_tol=TOL)
-    band = np.abs(u - o["accept"]) <= TOL * np.maximum(o["accept"], 1e-30)
+    band = np.abs(u - o["accept"]) <= MASK_BAND * np.maximum(o["accept"], 1e-30)
     np.testing.assert_array_equal(g["mask"][~band], o["mask"][~band])
     if batch:      # rows == all rows
         mask = g["mask"].astype(np.int32)
@@ -79,8 +83,8 @@ def _check(w, buf, rows, flags=0, batch=True):
         st = buf.stats()
         assert st.n_valid == b.n_valid and st.n_accept == b.n_accept and st.error_flags == 0
         pu._close(st.kappa, b.kappa, TOL, "kappa")
-        pu._close(g["w_obrs"], w_want, 2 * TOL, "w_OBRS")
-        pu._close(g["rho"], rho_want, 2 * TOL, "rho")
+        pu._close(g["w_obrs"], w_want, TOL, "w_OBRS")
+        pu._close(g["rho"], rho_want, TOL, "rho")
     return n_swapped
 
 
@@ -148,18 +152,67 @@ def test_lmhead_rejects_bad_arguments():
     assert e.value.status == obrs.JP_ERR_WORKSPACE
 
 
+def _materialised_fp32(w):
+    """The same logits through an independent fp32 GEMM of the harness (torch.mm on the widened bf16
+    values, row blocks), then the materialised two-tensor path on them."""
+    T, V = w.T, w.V
+    la = torch.empty((T, V), dtype=torch.float32, device=DEV)
+    lp = torch.empty((T, V), dtype=torch.float32, device=DEV)
+    Wa, Wp = w.W_actor.float(), w.W_policy.float()
+    for r0 in range(0, T, 2048):
+        torch.mm(w.H_actor[r0:r0 + 2048].float(), Wa, out=la[r0:r0 + 2048])
+        torch.mm(w.H_policy[r0:r0 + 2048].float(), Wp, out=lp[r0:r0 + 2048])
+    del Wa, Wp
+    wm = wl.Workload("materialised", la, lp, w.sampled_ids, w.uniforms, lam=w.lam, k=w.k, c1=w.c1, c2=w.c2)
+    bm = obrs.run_workload(wm)
+    torch.cuda.synchronize()
+    return bm
+
+
 def test_lmhead_full_size():
-    """T=16384, d=2048/4096, V=151936, k=64: sampled rows against the oracle, batch statistics
-    through their defining relations on the per-row outputs."""
+    """T=16384, d=2048/4096, V=151936, k=64.  256 seeded rows (and the first and last) against the
+    oracle on float64 logits; the batch stage (Sec. 4.4.2, Alg. 1 step 3), which needs every row,
+    against the materialised path run on logits from an independent fp32 GEMM of the harness (that
+    path is compared with the oracle over whole batches elsewhere)."""
     print("lm_head full size: T=16384 V=151936 d=(2048,4096) k=64", flush=True)
     w = wl.lm_head(device=DEV)
     buf = _run(w, 0, 0)
-    rows = np.array([0, 1, 4099, 8191, 12000, 16382, 16383])
+    rng = np.random.default_rng(20260210)
+    rows = np.unique(np.concatenate([[0, 1, w.T - 2, w.T - 1], rng.integers(0, w.T, 256)]))
+    assert len(rows) >= 256
     n_swapped = _check(w, buf, rows, 0, batch=False)
-    print(f"  lists with a near-tie swap among {2 * len(rows)}: {n_swapped}", flush=True)
-    st = buf.stats()
-    g = {n: buf.tensors[n].cpu().numpy().astype(np.float64) for n in ("accept_prob", "z_approx", "logratio", "w_obrs", "mask")}
-    assert st.error_flags == 0 and st.n_valid == w.T and st.n_accept == int(g["mask"].sum())
+    print(f"  {len(rows)} rows against the oracle; lists with a near-tie swap among {2 * len(rows)}: {n_swapped}", flush=True)
+
+    bm = _materialised_fp32(w)
+    st, sm = buf.stats(), bm.stats()
+    g = {n: buf.tensors[n].cpu().numpy().astype(np.float64) for n in buf.tensors if n != "stats"}
+    m = {n: bm.tensors[n].cpu().numpy().astype(np.float64) for n in bm.tensors if n != "stats"}
+    assert st.error_flags == 0 and sm.error_flags == 0 and st.n_valid == w.T == sm.n_valid
+    u = w.uniforms.cpu().numpy().astype(np.float64)
+    band = np.abs(u - m["accept_prob"]) <= MASK_BAND * np.maximum(m["accept_prob"], 1e-30)
+    np.testing.assert_array_equal(g["mask"][~band], m["mask"][~band])
+    assert abs(st.n_accept - sm.n_accept) <= int(band.sum())
+    pu._close(g["logq"], m["logq"], 0.0, "log q(x) vs materialised", abs_tol=TOL)
+    pu._close(g["logp"], m["logp"], 0.0, "log p(x) vs materialised", abs_tol=TOL)
+    pu._close(g["accept_prob"], m["accept_prob"], TOL, "a(x) vs materialised")
+    same = (g["topk_actor"] == m["topk_actor"]).all(axis=1) & (g["topk_policy"] == m["topk_policy"]).all(axis=1)
+    print(f"  rows whose two id lists equal the materialised path's: {int(same.sum())} of {w.T}", flush=True)
+    assert same.mean() > 0.9
+    # A near-tie swap exchanges two tokens of almost equal logit under one model at the k-th place of
+    # its list; their terms min(q, p/lambda) may differ by up to that k-th probability, about
+    # Z_approx / k on these flat rows.  Per-row values are compared where the lists agree, batch
+    # means with that allowance for the rows where they do not.
+    slack = TOL + (1.0 - same.mean()) * 2.0 / w.k
+    pu._close(g["z_approx"][same], m["z_approx"][same], TOL, "Z_approx vs materialised")
+    pu._close(st.mean_z_approx, sm.mean_z_approx, slack, "mean Z_approx vs materialised")
+    pu._close(st.mean_accept, sm.mean_accept, TOL, "mean a vs materialised")
+    adj = sm.alpha_hat / st.alpha_hat            # 1 unless a uniform inside the band fell on the other side
+    pu._close(st.kappa * adj, sm.kappa, slack, "kappa vs materialised")
+    pu._close(g["w_obrs"][same] * adj, m["w_obrs"][same], slack, "w_OBRS vs materialised")
+    # the batch stage's own relations on the per-row outputs
+    assert st.n_accept == int(g["mask"].sum())
     assert st.kappa == pytest.approx(g["mask"].mean() / g["z_approx"].mean(), rel=1e-9)
     np.testing.assert_allclose(g["w_obrs"], st.kappa * g["z_approx"] * np.maximum(w.lam, np.exp(g["logratio"])), rtol=1e-5)
-    print(f"  alpha_hat={st.alpha_hat:.4f} mean Z_approx={st.mean_z_approx:.4f} kappa={st.kappa:.4f}", flush=True)
+    np.testing.assert_allclose(g["rho"], np.minimum(g["w_obrs"], w.c1), rtol=1e-6)
+    print(f"  alpha_hat={st.alpha_hat:.4f} mean Z_approx={st.mean_z_approx:.4f} kappa={st.kappa:.4f} "
+          f"(materialised fp32 path: {sm.alpha_hat:.4f} {sm.mean_z_approx:.4f} {sm.kappa:.4f})", flush=True)

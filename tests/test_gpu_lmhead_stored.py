@@ -23,6 +23,7 @@ if torch.cuda.is_available():
 
 DEV = "cuda"
 TOL = 1e-3
+MASK_BAND = 1e-4      # fp32-accumulated logits: a(x) carries a few 1e-5 of relative rounding
 TIE = 1e-4
 WANT = ["accept_prob", "mask", "logq", "logp", "logratio", "z_approx", "w_obrs", "rho", "union_size",
         "topk_policy", "topk_policy_logp", "stats"]
@@ -113,7 +114,7 @@ def run_case(w, rule, rows, flags=0, vocab_chunk=0, stored=None, batch=True):
         pu._close(g["z_approx"][i], z_ref[i], TOL, "Z_approx")
         if flags & obrs.JP_FLAG_TOPK_LOGPROBS:
             pu._close(g["topk_policy_logp"][i], l[got] - o["lse_p"][i], 0.0, "top-k log p", abs_tol=TOL)
-    band = np.abs(u - o["accept"]) <= TOL * np.maximum(o["accept"], 1e-30)
+    band = np.abs(u - o["accept"]) <= MASK_BAND * np.maximum(o["accept"], 1e-30)
     np.testing.assert_array_equal(g["mask"][v & ~band], o["mask"][v & ~band])
     if batch:                                              # rows == all rows
         rows_for_batch = o.copy()
@@ -124,8 +125,8 @@ def run_case(w, rule, rows, flags=0, vocab_chunk=0, stored=None, batch=True):
         st = buf.stats()
         assert st.n_valid == b.n_valid and st.n_accept == b.n_accept and st.error_flags == 0
         pu._close(st.kappa, b.kappa, TOL, "kappa")
-        pu._close(g["w_obrs"][v], w_want[v], 2 * TOL, "w_OBRS")
-        pu._close(g["rho"][v], rho_want[v], 2 * TOL, "rho")
+        pu._close(g["w_obrs"][v], w_want[v], TOL, "w_OBRS")
+        pu._close(g["rho"][v], rho_want[v], TOL, "rho")
     return buf, n_swapped
 
 
@@ -265,7 +266,8 @@ def test_full_size_sampled_rows():
     _say("lm_head + stored actor, full size: T=16384 V=151936 d_policy=4096 k=64")
     w = wl.lm_head(device=DEV)
     T, k = w.T, w.k
-    rows = np.array([0, 1, 4099, 8191, 12000, 16382, 16383])
+    rng = np.random.default_rng(20260211)
+    rows = np.unique(np.concatenate([[0, 1, T - 2, T - 1], rng.integers(0, T, 256)]))
     # The stored side is needed for every row: an arbitrary but valid one (ids spread over the
     # vocabulary, log-probabilities of a geometric tail) except on the sampled rows, which get the
     # actor head's true top-k.  The comparison is against the oracle on the same stored inputs.

@@ -201,3 +201,27 @@ def test_forward_can_be_captured_in_a_hip_graph():
             same = torch.equal(buf.tensors[n], ref[n]) or (
                 ref[n].is_floating_point() and torch.equal(torch.nan_to_num(buf.tensors[n]), torch.nan_to_num(ref[n])))
             assert same, (rep, n)
+
+
+@pytest.mark.parametrize("k", [8, 200])
+def test_bf16_vocabulary_beyond_16_bit_chunk_indices(k):
+    """bf16 rows of more than 65 535 16-byte chunks (V > 524 280) take 64-bit chunk descriptors: several
+    hundred full iterations, a partial one, a ragged tail, ties (bf16 values repeat at this V), negative
+    and -inf entries, a constant row, and a row whose largest values sit in the last chunks."""
+    V = 524288 + 8 * 37 + 3
+    T = 6
+    _say(f"bf16 T={T} V={V} k={k}: 64-bit chunk descriptors")
+    w = wl.make_logits(T, V, torch.bfloat16, seed=4242 + k, device=DEV, spikes=5, noise_sigma=0.8
+                       ).with_params(lam=0.9, k=k)
+    w.actor[1, :] = -3.0                                  # all tied and negative: ids 0..k-1
+    w.actor[2, :] = torch.linspace(-9.0, 4.0, V, device=DEV).to(torch.bfloat16)   # best values in the last chunks
+    w.policy[2, :] = torch.linspace(4.0, -9.0, V, device=DEV).to(torch.bfloat16)
+    w.actor[3, 1000:400000] = float("-inf")               # masked entries never beat a finite logit
+    w.policy[4, V - 2] = 30.0                             # the ragged tail chunk holds the maximum
+    w.sampled_ids[1] = V - 1
+    w.sampled_ids[2] = 524281                             # a token past the 16-bit chunk range
+    w.sampled_ids[3] = 7
+    buf, R, st = pu.check_all(w, ALL_FLAGS)
+    assert buf.topk_actor[1].cpu().tolist() == list(range(k))
+    assert int(buf.topk_policy[4, 0]) == V - 2
+    assert int(buf.topk_actor[2, 0]) >= V - 1000           # the first of the ~300 tokens that round to 4.0

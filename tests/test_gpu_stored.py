@@ -157,3 +157,21 @@ def test_full_size_sampled_rows():
     zd = buf.z_approx
     zf = full.z_approx
     assert torch.all(zd <= zf * (1 + 2e-3)) and torch.all(zf <= zk * (1 + 2e-3))
+
+
+@pytest.mark.parametrize("k,rule", [(8, 1), (200, 2)])
+def test_bf16_vocabulary_beyond_16_bit_chunk_indices(k, rule):
+    """bf16 rows of more than 65 535 16-byte chunks (V > 524 280): the 64-bit chunk descriptors of the
+    stored-actor form, with ties, a ragged tail and stored ids past the 16-bit chunk range."""
+    V = 524288 + 8 * 21 + 5
+    T = 5
+    _say(f"stored form: bf16 T={T} V={V} k={k} rule={rule}: 64-bit chunk descriptors")
+    w = wl.make_logits(T, V, torch.bfloat16, seed=5151 + k, device=DEV, spikes=4, noise_sigma=1.1
+                       ).with_params(lam=1.1, k=k)
+    w.policy[1, :] = 0.5                                  # all tied: ids 0..k-1
+    w.policy[2, V - 3] = 25.0                             # the ragged tail chunk holds the maximum
+    w.actor[3, V - 70000:] += 6.0                         # the stored list lies past the 16-bit chunk range
+    w.sampled_ids[3] = V - 1
+    buf, R, st = run_case(w, rule, flags=obrs.JP_FLAG_TOPK_LOGPROBS)
+    assert buf.topk_policy[1].cpu().tolist() == list(range(k))
+    assert int(buf.topk_policy[2, 0]) == V - 3
