@@ -211,8 +211,8 @@ def test_bf16_vocabulary_beyond_16_bit_chunk_indices(k):
     V = 524288 + 8 * 37 + 3
     T = 6
     _say(f"bf16 T={T} V={V} k={k}: 64-bit chunk descriptors")
-    w = wl.make_logits(T, V, torch.bfloat16, seed=4242 + k, device=DEV, spikes=5, noise_sigma=0.8
-                       ).with_params(lam=0.9, k=k)
+    w = wl.make_logits(T, V, torch.bfloat16, seed=4242 + k, device=DEV, spikes=5, noise_sigma=0.8,
+                       row_stride=(V + 7) // 8 * 8 + 8).with_params(lam=0.9, k=k)
     w.actor[1, :] = -3.0                                  # all tied and negative: ids 0..k-1
     w.actor[2, :] = torch.linspace(-9.0, 4.0, V, device=DEV).to(torch.bfloat16)   # best values in the last chunks
     w.policy[2, :] = torch.linspace(4.0, -9.0, V, device=DEV).to(torch.bfloat16)

@@ -166,8 +166,8 @@ def test_bf16_vocabulary_beyond_16_bit_chunk_indices(k, rule):
     V = 524288 + 8 * 21 + 5
     T = 5
     _say(f"stored form: bf16 T={T} V={V} k={k} rule={rule}: 64-bit chunk descriptors")
-    w = wl.make_logits(T, V, torch.bfloat16, seed=5151 + k, device=DEV, spikes=4, noise_sigma=1.1
-                       ).with_params(lam=1.1, k=k)
+    w = wl.make_logits(T, V, torch.bfloat16, seed=5151 + k, device=DEV, spikes=4, noise_sigma=1.1,
+                       row_stride=(V + 7) // 8 * 8).with_params(lam=1.1, k=k)
     w.policy[1, :] = 0.5                                  # all tied: ids 0..k-1
     w.policy[2, V - 3] = 25.0                             # the ragged tail chunk holds the maximum
     w.actor[3, V - 70000:] += 6.0                         # the stored list lies past the 16-bit chunk range
