@@ -21,14 +21,55 @@ sys.path.insert(0, ROOT)
 METRIC = "OBRS tokens/sec at V=151936 bf16 on 1 MI355X; achieved HBM GB/s vs peak"
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (see profiles/), scaled by the counter reading of a plain copy of known size.
-# None until measured for the workload below.
-MEASURED_TRAFFIC_BYTES = {
-    # (T, V, k): FETCH_SIZE 2 545 790 KiB x 2.0 + WRITE_SIZE 6 461 KiB x 1.0
-    # (profiles/row_kernel_rollout_T8192_V151936_k64.md)
-    (8192, 151936, 64): int(2545790 * 1024 * 2.0 + 6461 * 1024 * 1.0),
-}
+KERNEL_SOURCES = ("paper_2602_06107_amd/csrc/jp_row_kernel.hip", "paper_2602_06107_amd/csrc/jp_device_utils.h",
+                  "paper_2602_06107_amd/csrc/jp_obrs_internal.h")
+
+
+def kernel_source_digest() -> str:
+    """sha256 over the sources of the row kernel: a traffic record only counts for the code it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(T: int, V: int, k: int):
+    """HBM bytes per row-kernel launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
+    summaries are committed under profiles/ (a line `traffic_record: {json}` in the summary, KiB per
+    dispatch and the factors a plain copy of known size gave in the same run).  Returns
+    (bytes or None, where it came from / why not): None when no record covers this workload or the
+    kernel sources have changed since the record was taken."""
+    import glob
+    digest = kernel_source_digest()
+    stale = None
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        with open(path) as f:
+            for line in f:
+                if not line.startswith("traffic_record:"):
+                    continue
+                rec = json.loads(line[len("traffic_record:"):])
+                if (rec.get("kernel"), rec.get("T"), rec.get("V"), rec.get("k")) != ("row_kernel", T, V, k):
+                    continue
+                if rec.get("kernel_source_sha256") != digest:
+                    stale = "record in profiles/%s was taken on other kernel sources (%s, now %s)" % (
+                        os.path.basename(path), rec.get("kernel_source_sha256"), digest)
+                    continue
+                nbytes = int(rec["fetch_kib"] * 1024 * rec["fetch_factor"] + rec["write_kib"] * 1024 * rec["write_factor"])
+                return nbytes, "profiles/" + os.path.basename(path)
+    return None, stale or "no traffic record for this workload under profiles/"
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def algorithmic_bytes_per_token(V: int, k: int, esz: int) -> int:
@@ -143,6 +184,8 @@ def main():
                          "budget, three sweeps) and report it as \"lambda_for_budget\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows-single", type=int, default=256,
+                    help="rows the CPU oracle is timed on with ONE thread, for a per-core figure (0 = skip)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -196,7 +239,37 @@ def main():
     row_ms_avg = sum(row_ms) / len(row_ms)
     algo_bytes = algorithmic_bytes_per_token(V, w.k, esz) * T
     achieved = algo_bytes / (row_ms_avg * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((T, V, w.k))
+    traffic, traffic_source = measured_traffic(T, V, w.k)
+
+    # the attainable read-only ceiling of this machine, from code in the tree: the one-tensor sweep
+    # of jp_obrs_token_logprob (log-sum-exp + one gather, nothing else), timed the same way
+    lp_tmp = torch.empty(T, dtype=torch.float32, device=dev)
+    cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps + 1)]
+    for a, b in cev:
+        a.record()
+        obrs.jp_obrs_token_logprob(w.policy, w.sampled_ids, lp_tmp)
+        b.record()
+    torch.cuda.synchronize()
+    c_ms = sorted(a.elapsed_time(b) for a, b in cev[1:])
+    c_avg = sum(c_ms) / len(c_ms)
+    ceiling = {"kernel": "token_logprob_kernel<bf16> (one tensor, read only)", "kernel_ms_avg": c_avg,
+               "achieved": T * (V * esz + 8) / (c_avg * 1e-3) / 1e9, "unit": "GB/s"}
+
+    # JP_FLAG_EXACT_Z: what the second sweep costs and how much of Z the top-k estimate holds
+    exact_info = None
+    if args.flags & 1:
+        xev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps + 1)]
+        for a, b in xev:
+            a.record()
+            obrs.jp_obrs_rows(w.actor, w.policy, w.sampled_ids, w.uniforms, w.lam, w.k, args.flags, buf)
+            b.record()
+        torch.cuda.synchronize()
+        x_ms = sorted(a.elapsed_time(b) for a, b in xev[1:])
+        x_avg = sum(x_ms) / len(x_ms)
+        ratio = (buf.z_approx.double() / buf.z_exact.double())
+        exact_info = {"rows_plus_exact_z_ms_avg": x_avg, "exact_z_extra_ms": x_avg - row_ms_avg,
+                      "z_approx_over_z_exact_mean": float(ratio.mean()), "z_approx_over_z_exact_min": float(ratio.min()),
+                      "mean_z_exact": st.mean_z_exact, "mean_z_approx": st.mean_z_approx, "k": w.k}
 
     grad_info = None
     if args.grad != "none":
@@ -306,8 +379,16 @@ def main():
         orc.batch(R.out, R.out["mask"], w.lam, w.c1, w.c2)
         cw = time.perf_counter() - c0
         cpu = {"value": n / cw, "unit": "tokens/s", "cores": int(R.threads), "kind": "oracle",
+               "cpu_model": cpu_model(),
                "sample": f"first {n} of {T} rows of the same batch, float64 C oracle, "
                          f"{cw:.1f} s wall"}
+        n1 = min(args.cpu_rows_single, n)
+        if n1 > 0:
+            c0 = time.perf_counter()
+            R1 = orc.rows(a_np[:n1], p_np[:n1], x_np[:n1], u_np[:n1], w.lam, w.k, n_threads=1)
+            c1 = time.perf_counter() - c0
+            cpu["single_thread"] = {"value": n1 / c1, "unit": "tokens/s", "cores": int(R1.threads),
+                                    "sample": f"first {n1} rows, one thread, {c1:.1f} s wall"}
 
     line = {
         "metric": METRIC,
@@ -327,11 +408,15 @@ def main():
                    "logits_dtype": "bf16", "T": T, "V": V, "k": w.k, "lambda": w.lam, "flags": args.flags,
                    "kappa": st.kappa, "alpha_hat": st.alpha_hat},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "traffic_over_algorithmic": (traffic / algo_bytes) if traffic else None,
+                     "read_only_ceiling": ceiling,
                      "kernel": "row_kernel<bf16,key32,%d>" % (64 if w.k <= 64 else 128 if w.k <= 128 else 256), "kernel_ms_avg": row_ms_avg,
                      "kernel_ms_min": row_ms[0], "algorithmic_bytes": algo_bytes},
         "cpu_baseline": cpu,
     }
+    if exact_info is not None:
+        line["exact_z"] = exact_info
     if grad_info is not None:
         line["distill_grad"] = grad_info
     if stored_info is not None:

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libjp_obrs.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
-SOURCES = ["jp_obrs_kernels.hip", "jp_lmhead_kernels.hip", "jp_obrs_api.hip"]
+SOURCES = ["jp_row_kernel.hip", "jp_obrs_kernels.hip", "jp_lmhead_kernels.hip", "jp_obrs_api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
