@@ -181,7 +181,7 @@ def main():
                          "more logit tensor, one sweep) and report it as \"token_logprob\"")
     ap.add_argument("--budget", type=float, default=0.0,
                     help="also time jp_obrs_lambda_for_budget (per-row lambda that meets this acceptance "
-                         "budget, three sweeps) and report it as \"lambda_for_budget\"")
+                         "budget) and the one-lambda-per-batch variant, and report them as \"lambda_for_budget\"")
     ap.add_argument("--cpu-rows", type=int, default=4096,
                     help="rows of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--cpu-rows-single", type=int, default=256,
@@ -350,12 +350,23 @@ def main():
         torch.cuda.synchronize()
         b_ms = sorted(a.elapsed_time(b) for a, b in bev[1:])
         b_avg = sum(b_ms) / len(b_ms)
-        b_bytes = 3 * T * 2 * V * esz                      # three sweeps of both rows
+        # two sweeps of both rows is what the search needs on this recipe (one approximate, one exact);
+        # a row that needs more moves more bytes than it is credited with here
+        b_bytes = 2 * T * 2 * V * esz
         budget_info = {"kernel": "budget_kernel<bf16>", "abar": args.budget, "kernel_ms_avg": b_avg,
-                       "kernel_ms_min": b_ms[0], "algorithmic_bytes": b_bytes, "bound": "hbm",
+                       "kernel_ms_min": b_ms[0], "sweeps_credited": 2, "algorithmic_bytes": b_bytes, "bound": "hbm",
                        "achieved": b_bytes / (b_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": b_bytes / (b_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "mean_lambda": float(lam_out.double().mean())}
+        one = torch.empty(1, dtype=torch.float32, device=dev)
+        b_scratch = torch.empty(obrs._lib.jp_obrs_budget_scratch_bytes(), dtype=torch.uint8, device=dev)
+        for a, b in bev:
+            a.record()
+            obrs.jp_obrs_lambda_for_budget_batch(w.actor, w.policy, args.budget, buf, out=one, scratch=b_scratch)
+            b.record()
+        torch.cuda.synchronize()
+        bb_ms = sorted(a.elapsed_time(b) for a, b in bev[1:])
+        budget_info["batch"] = {"call_ms_avg": sum(bb_ms) / len(bb_ms), "call_ms_min": bb_ms[0], "lambda": float(one.item())}
 
     if args.calibrate_copy > 0:
         scratch = torch.empty_like(w.actor)

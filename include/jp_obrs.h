@@ -304,11 +304,18 @@ jp_status jp_obrs_forward3(const void *actor_logits, const void *policy_new_logi
  *   sum_v q_t(v) min(1, p_t(v) / (lambda_t q_t(v))) = abar_t,   abar_t = row_target ? row_target[t] : target,
  * i.e. the threshold at which the OBRS rule accepts exactly the fraction abar_t of the proposals.
  * For abar_t = 1 (every lambda up to min_v p/q accepts everything) the largest such lambda is
- * returned.  Three sweeps of the two logit tensors; the log-sum-exps and the row status come from
- * `workspace`, where a preceding jp_obrs_rows / jp_obrs_forward call on the SAME tensors and T
- * left them.  Accuracy: the bracket is narrowed to 128 / 64^3 in log2 lambda and the last step is
- * the closed form on that piece, so the budget is met to the float tolerance of the other outputs;
- * lambda itself is only as well determined as the budget determines it (near abar = 1 it is not).
+ * returned.  The log-sum-exps and the row status come from `workspace`, where a preceding
+ * jp_obrs_rows / jp_obrs_forward call on the SAME tensors and T left them.
+ * Cost: two sweeps of the two logit tensors on ordinary rows (one that locates the crossing to
+ * 3/16 in log2 lambda from an approximate histogram, one exact over 256 bins of that bracket), up
+ * to six on degenerate ones (the crossing outside the resolved ratios 2^-16 .. 2^16, a single
+ * token that carries a visible part of the budget next to the crossing, abar at the keepable mass).
+ * Accuracy: the last step is the closed form lambda = B / (abar - A) on the crossing bin, exact up
+ * to the tokens inside that bin; the search ends when their q-mass times (2^bin width - 1) is
+ * below 1e-4 abar (bf16 logits) or 1e-6 abar (fp32), or the bin is narrower than 1e-6, so the
+ * budget is met to the float tolerance of the other outputs; lambda itself is only as well
+ * determined as the budget determines it (near abar = 1 it is not).  Ratios are searched over
+ * [2^-64, 2^64].
  *   out_lambda: device [T] fp32; padding rows 0; rows with data errors, or a budget outside (0, 1], NaN.
  * target is checked on the host (JP_ERR_PARAM) when row_target is NULL.
  */
@@ -321,7 +328,10 @@ jp_status jp_obrs_lambda_for_budget(const void *actor_logits, const void *policy
  * One scaling factor for a whole batch: the lambda with (1/n) sum_t Z_t(lambda) = target over the n
  * valid rows (the mean acceptance of the batch under one global lambda, which is how Sec. 4 uses
  * lambda).  Same search as jp_obrs_lambda_for_budget with the histogram bins summed over the rows
- * in device memory; three sweeps of the two tensors, nothing passes through the host.
+ * in device memory (64-bit fixed point: the sums do not depend on the order of the rows) and a
+ * one-wave kernel between the sweeps that picks the next bracket; nothing passes through the host.
+ * The launch sequence is fixed (six sweep kernels and the smallest-ratio sweep, each of which
+ * returns at once when the search has ended), so the call can be captured.
  *   out_lambda: device, one fp32 (NaN if the batch has no valid row)
  *   scratch:    device, jp_obrs_budget_scratch_bytes() bytes, 16-byte aligned, contents irrelevant
  * workspace as for jp_obrs_lambda_for_budget.

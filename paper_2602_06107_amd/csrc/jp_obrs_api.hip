@@ -596,6 +596,7 @@ jp_status jp_obrs_lambda_for_budget(const void *actor_logits, const void *policy
     b.actor = actor_logits; b.policy = policy_logits; b.T = T; b.V = V; b.stride = row_stride;
     b.lse_q = w.lse_q; b.lse_p = w.lse_p; b.rowflag = w.rowflag;
     b.row_target = row_target; b.target = target; b.lambda_out = out_lambda;
+    b.eps_rel = dt == JP_BF16 ? 1e-4f : 1e-6f;         // a tenth of the float tolerance of the other outputs
     if (jp::launch_budget(b, (int)dt, (hipStream_t)stream) != hipSuccess) return JP_ERR_HIP;
     return JP_OK;
 }
@@ -622,6 +623,7 @@ jp_status jp_obrs_lambda_for_budget_batch(const void *actor_logits, const void *
     b.actor = actor_logits; b.policy = policy_logits; b.T = T; b.V = V; b.stride = row_stride;
     b.lse_q = w.lse_q; b.lse_p = w.lse_p; b.rowflag = w.rowflag;
     b.row_target = nullptr; b.target = target; b.lambda_out = nullptr;
+    b.eps_rel = dt == JP_BF16 ? 1e-4f : 1e-6f;
     if (jp::launch_budget_batch(b, (int)dt, (jp::BudgetBatchState *)scratch, out_lambda, (hipStream_t)stream) != hipSuccess)
         return JP_ERR_HIP;
     return JP_OK;

@@ -105,6 +105,7 @@ struct BudgetArgs {
     const float *row_target;          // [T] or nullptr
     float target;
     float *lambda_out;                // [T]
+    float eps_rel;                    // error of Z, relative to the budget, below which the search stops
 };
 
 // Device-resident state of the per-batch budget search (in the caller's scratch buffer).
@@ -113,7 +114,8 @@ struct BudgetBatchState {
     int done, dmin_ord;               // finished flag; smallest log2 ratio as an order-preserving int
     double lambda;
     unsigned long long n_rows, above, below;   // valid rows; mass outside the bracket (2^-32 units)
-    unsigned long long bq[64], bp[64];         // bin sums over all rows (2^-32 units)
+    unsigned long long coarse[512];            // first sweep: q-mass per coarse bin over all rows (2^-31 units)
+    unsigned long long fq[256], fp[256];       // exact sweeps: q- and p-mass per fine bin over all rows (2^-32 units)
 };
 
 hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st);

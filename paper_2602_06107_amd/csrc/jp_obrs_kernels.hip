@@ -161,103 +161,46 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
 // Scaling factor for an acceptance budget (Sec. 3.3, Theorem 2): per row the lambda with
 // Z(lambda) = sum_v min(q_v, p_v / lambda) = abar.  With d_v = log2(p_v / q_v),
 //   Z(2^x) = sum_{d_v > x} q_v + 2^-x sum_{d_v <= x} p_v
-// is non-increasing in x, so the crossing is bracketed by histogram passes: a pass sweeps the row,
-// adds q_v and p_v of the tokens inside the current bracket [lo, hi) to 64 bins in LDS (float64
-// atomics; the bins belong to this wave alone and the hardware takes the lanes of an instruction in
-// a fixed order, so the sums are reproducible; 8 copies per bin keep same-address collisions to
-// eight lanes) and the mass outside it to two per-lane sums; the bin whose edges straddle abar is
-// the next bracket.  After BUDGET_PASSES passes the bracket is 128 / 64^3 = 4.9e-4 wide in log2
-// lambda and lambda = B / (abar - A) with A the q-mass above it and B the p-mass at or below it;
-// that closed form is exact up to the few tokens whose ratio lies inside the last bracket (their
-// mass times the bracket width, ~1e-8 of Z for a vocabulary of 1e5 tokens).
-// abar = 1 returns the smallest ratio (the largest lambda that still accepts everything).
+// is non-increasing in x, so the crossing is bracketed by histogram sweeps of the row pair.
+//   * The first sweep only has to say roughly where the crossing is: it puts the q-mass of every
+//     token into 512 bins of width 1/16 over [-16, 16), the first and the last bin also taking
+//     what lies beyond, out to +-64 (one exponential and one 32-bit integer LDS atomic per token:
+//     2^-31 units, rounded, two copies per bin against same-address collisions) and prices the
+//     p-mass of a bin as its q-mass times 2^(bin centre).  Inside the resolved part that is off by
+//     at most a factor 2^(+-1/32) on every token; the bracket for the next sweep is the bin of the
+//     crossing found that way with a bin on either side.  Narrow bins matter twice: lanes of one
+//     instruction seldom meet in a bin, and few tokens fall into the bracket of the next sweep.
+//   * Every later sweep is exact: the mass outside the bracket [lo, hi) goes to per-lane sums (one
+//     exponential per token: p below the bracket, q above it), the tokens inside it to 256 fine bins
+//     (fp32 LDS atomics; the bins belong to this wave alone and the hardware takes the lanes of an
+//     instruction in a fixed order, so the sums are reproducible).  If the crossing is not inside
+//     after all (a degenerate row), the bracket moves to that side and widens; if it is, the sweep
+//     ends with the closed form lambda = B / (abar - A) on the crossing bin, A the q-mass above it
+//     and B the p-mass at or below it, which is exact up to the tokens inside that one bin: their
+//     mass times the bin width.  Where that product is not negligible against the budget (a heavy
+//     token next to the crossing), one more sweep splits the bin again.
+// On the rollout shape two sweeps are enough (fine bins 0.0007 wide in log2 lambda).
+// abar at the keepable mass (abar = 1) returns the smallest ratio, the largest lambda that still
+// accepts everything.
 // =================================================================================================
-constexpr int BUDGET_BINS = 64, BUDGET_COPIES = 8, BUDGET_PASSES = 3;
-constexpr float BUDGET_RANGE = 64.f;                       // first bracket: ratios in [2^-64, 2^64)
+constexpr int BUDGET_COARSE = 512, BUDGET_FINE = 256, BUDGET_MAX_SWEEPS = 6;
+constexpr float BUDGET_RANGE = 64.f;                       // the search covers ratios in [2^-64, 2^64)
+constexpr float BUDGET_CRANGE = 16.f;                      // the coarse bins resolve [2^-16, 2^16): the first and
+                                                           // the last one also take what lies beyond, out to the range
+constexpr float BUDGET_COARSE_W = 2.f * BUDGET_CRANGE / (float)BUDGET_COARSE;
+constexpr int BUDGET_CPL = BUDGET_COARSE / WAVE, BUDGET_FPL = BUDGET_FINE / WAVE;    // bins per lane
+constexpr double BUDGET_FIX31 = 2147483648.0;              // 2^31
 
-// x in [0, 1] as an integer multiple of 2^-40, truncated: the 24-bit significand shifted into place.
-// (Integer LDS atomics take same-address collisions faster than float64 ones; the first pass, where
-// most tokens share a few bins, uses them.)
-constexpr double BUDGET_FIX40 = 1099511627776.0;           // 2^40
-__device__ __forceinline__ unsigned long long to_fixed40(float x)
-{
-    const uint32_t bits = __float_as_uint(x);
-    const uint32_t m = (bits & 0x7fffffu) | 0x800000u;      // significand with its leading one
-    uint32_t sh = 142u - (bits >> 23);                      // x = m 2^(e-150): (m 2^32) >> (142 - e) = x 2^40
-    sh = sh < 63u ? sh : 63u;                               // below 2^-40 (and zero): nothing left
-    return ((unsigned long long)m << 32) >> sh;
-}
-
-// One histogram sweep of a row pair for the bracket [lo, hi): q- and p-mass of the tokens inside it
-// go to the LDS bins hq / hp, the mass outside it to the per-lane sums qa (above) and
-// pb (below).  The first pass (FIRST) covers every ratio: it runs without branches, puts a ratio
-// beyond the range into the nearest edge bin (the later passes sum the mass outside their bracket
-// themselves, so this only has to find the bracket) and tracks the smallest log2 ratio.
-template <class ET, bool FIRST>
-__device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
-                                             float lo, float hi, double *hq,
-                                             double *hp, double &qa, double &pb, float &dmin)
+// Sweep of one row pair with `account(fq, fp)` called on every chunk (padding of the ragged last
+// chunk arrives as -inf in both rows: probability 0 under both models).
+template <class ET, class F>
+__device__ __forceinline__ void budget_for_each_chunk(const char *rowq, const char *rowp, int64_t V, F account)
 {
     constexpr int VEC = ET::VEC;
     const int lane = threadIdx.x;
     const uint32_t nfull = (uint32_t)(V / VEC);
     const int tail = (int)(V - (int64_t)nfull * VEC);
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
-    const int copy = lane & (BUDGET_COPIES - 1);
-    for (int e = lane; e < BUDGET_BINS * BUDGET_COPIES; e += WAVE) { hq[e] = 0.0; hp[e] = 0.0; }   // all bits zero: also integer 0
-    lds_sync();
-    const float inv_w = (float)BUDGET_BINS / (hi - lo);
-    qa = 0.0;
-    pb = 0.0;
-    auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
-        if constexpr (FIRST) {
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), ap = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
-                const float d = ap - aq;
-                // A ratio below the range keeps none of its q-mass at any lambda of the range, one
-                // above it pays none of its p-mass; NaN (both probabilities 0) adds two zeros to bin 0.
-                int b = (int)((d - lo) * inv_w);
-                b = b < 0 ? 0 : (b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1);
-                const float qv = d >= lo ? __builtin_amdgcn_exp2f(aq) : 0.f;
-                const float pv = d < hi ? __builtin_amdgcn_exp2f(ap) : 0.f;
-                atomicAdd((unsigned long long *)&hq[b * BUDGET_COPIES + copy], to_fixed40(qv));
-                atomicAdd((unsigned long long *)&hp[b * BUDGET_COPIES + copy], to_fixed40(pv));
-                // the smallest ratio among tokens that both models can emit (finite d)
-                dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
-            }
-        } else {
-            float pbf = 0.f, qaf = 0.f;                 // this chunk's mass below / above the bracket
-            float dv[VEC], apv[VEC], one[VEC];
-            bool any = false;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq);
-                apv[j] = __builtin_fmaf(fp[j], LOG2E_F, -Ap);
-                dv[j] = apv[j] - aq;
-                // a token outside the bracket needs only one of its two probabilities: p below it, q above
-                const bool below = dv[j] < lo;
-                one[j] = __builtin_amdgcn_exp2f(below ? apv[j] : aq);
-                pbf += below ? one[j] : 0.f;            // at or below every lambda of the bracket
-                qaf += dv[j] >= hi ? one[j] : 0.f;      // above every lambda of the bracket
-                any |= dv[j] >= lo && dv[j] < hi;       // (both probabilities 0 give NaN: no mass)
-            }
-            pb += (double)pbf;
-            qa += (double)qaf;
-            // late passes: the bracket is narrow and most chunks of a wave hold nothing inside it
-            if (__ballot(any)) {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    if (dv[j] >= lo && dv[j] < hi) {
-                        int b = (int)((dv[j] - lo) * inv_w);
-                        b = b < BUDGET_BINS - 1 ? b : BUDGET_BINS - 1;
-                        atomicAdd(&hq[b * BUDGET_COPIES + copy], (double)one[j]);
-                        atomicAdd(&hp[b * BUDGET_COPIES + copy], (double)__builtin_amdgcn_exp2f(apv[j]));
-                    }
-                }
-            }
-        }
-    };
     const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
     if (nit > 0) {
         constexpr int D = 3;                            // loads in flight per tensor and lane
@@ -285,100 +228,273 @@ __device__ __forceinline__ void budget_sweep(const char *rowq, const char *rowp,
             }
         }
     }
-    {
-        const uint32_t c = nit * WAVE + lane;
-        if (c < nchunks) {
-            float fq[VEC], fp[VEC];
-            load_chunk<ET>(rowq, c, nfull, tail, fq);
-            load_chunk<ET>(rowp, c, nfull, tail, fp);
-            account(fq, fp);
-        }
-    }
-    lds_sync();
-}
-
-// Lane b's bin b summed over its copies: integers in 2^-40 units after the first pass, float64 after the others.
-__device__ __forceinline__ void budget_bin_sums(const double *hq, const double *hp, bool first_pass, double &q, double &p)
-{
-    const int lane = threadIdx.x;
-    if (first_pass) {
-        unsigned long long uq = 0, up = 0;
-#pragma unroll 4
-        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) {
-            uq += ((const unsigned long long *)hq)[lane * BUDGET_COPIES + c2];
-            up += ((const unsigned long long *)hp)[lane * BUDGET_COPIES + c2];
-        }
-        q = (double)uq / BUDGET_FIX40;
-        p = (double)up / BUDGET_FIX40;
-    } else {
-        q = 0.0; p = 0.0;
-#pragma unroll 4
-        for (int c2 = 0; c2 < BUDGET_COPIES; ++c2) { q += hq[lane * BUDGET_COPIES + c2]; p += hp[lane * BUDGET_COPIES + c2]; }
+    const uint32_t c = nit * WAVE + lane;
+    if (c < nchunks) {
+        float fq[VEC], fp[VEC];
+        load_chunk<ET>(rowq, c, nfull, tail, fq);
+        load_chunk<ET>(rowp, c, nfull, tail, fp);
+        account(fq, fp);
     }
 }
 
-// One step of the bracket search, run by a whole wave: lane b brings the q- and p-mass of bin b
-// (Qb, Pbin); A_above / B_below are the masses outside the bracket, `goal` the value Z must reach
-// (abar, or abar times the number of rows when the masses are sums over a batch); dmin the
-// smallest log2 ratio seen.  Narrows [lo, hi) to the bin that straddles the goal, or finishes
-// (returns true) with lambda.  sq_ / sp_: BUDGET_BINS doubles of LDS each.
-__device__ __forceinline__ bool budget_step(double goal, double A_above, double B_below, double Qb, double Pbin,
-                                            float &lo, float &hi, int pass, float dmin, double *sq_, double *sp_,
-                                            double &lambda)
+// First sweep: q-mass of every token into the coarse bins `hist` ([1 + bin][2 copies], 2^-31 units).
+// A ratio beyond the resolved part goes to the first or the last bin; one below the whole range (a
+// token the target cannot emit has d = -inf) keeps none of its q-mass at any lambda of the range and
+// goes to entry 0, which nobody reads.
+template <class ET>
+__device__ __forceinline__ void budget_coarse_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
+                                                    uint32_t *hist)
+{
+    constexpr int VEC = ET::VEC;
+    const int lane = threadIdx.x;
+    for (int e = lane; e < 2 * (BUDGET_COARSE + 1); e += WAVE) hist[e] = 0u;
+    lds_sync();
+    const float dA = Ap - Aq;
+    const float inv_w = 1.f / BUDGET_COARSE_W;
+    const float off = BUDGET_CRANGE * inv_w + 1.f;
+    const uint32_t copy = (uint32_t)lane & 1u;
+    budget_for_each_chunk<ET>(rowq, rowp, V, [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(fq[j], LOG2E_F, -Aq));
+            const float d = __builtin_fmaf(fp[j] - fq[j], LOG2E_F, -dA);          // log2(p / q); NaN when both are 0
+            int b = (int)__builtin_fmaf(d, inv_w, off);                           // 1 + bin (saturates; NaN gives 0: q is 0 then)
+            b = b < 1 ? (d >= -BUDGET_RANGE ? 1 : 0) : (b < BUDGET_COARSE ? b : BUDGET_COARSE);
+            atomicAdd(&hist[((uint32_t)b << 1) | copy], (uint32_t)__builtin_fmaf(q, (float)BUDGET_FIX31, 0.5f));
+        }
+    });
+    lds_sync();
+}
+
+// The smallest finite log2 ratio of a row pair (one more sweep, only for a budget at the keepable
+// mass, where every lambda up to the smallest ratio accepts everything).
+template <class ET>
+__device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap)
+{
+    constexpr int VEC = ET::VEC;
+    const float dA = Ap - Aq;
+    float dmin = __uint_as_float(0x7f800000u);
+    budget_for_each_chunk<ET>(rowq, rowp, V, [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float d = __builtin_fmaf(fp[j] - fq[j], LOG2E_F, -dA);
+            dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
+        }
+    });
+    return -uniform_f(wave_max(-dmin));
+}
+
+// A later sweep for the bracket [lo, hi): the exact mass outside it (qa above, pb below, per-lane
+// sums) and the q- and p-mass of the tokens inside it in the fine bins hq / hp (BUDGET_FINE + 1
+// entries each: a product that rounds up to the bin count lands in the extra one, which is folded
+// into the last bin).
+template <class ET>
+__device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
+                                                  float lo, float hi, float *hq, float *hp, double &qa, double &pb)
+{
+    constexpr int VEC = ET::VEC;
+    const int lane = threadIdx.x;
+    for (int e = lane; e < BUDGET_FINE + 1; e += WAVE) { hq[e] = 0.f; hp[e] = 0.f; }
+    lds_sync();
+    const float width = hi - lo;
+    const float inv_w = (float)BUDGET_FINE / width;
+    const float Apl = Ap + lo;
+    const uint32_t width_bits = __float_as_uint(width);
+    const float scale_below = __builtin_amdgcn_exp2f(lo);
+    double not_below = 0.0, below_p = 0.0;
+    budget_for_each_chunk<ET>(rowq, rowp, V, [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+        float nbf = 0.f, pbf = 0.f;
+        float dl[VEC], e[VEC];
+        bool any = false;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            // below the bracket a token pays p / lambda at every lambda of it, from the bracket up it
+            // keeps q: 2^min(aq, ap - lo) is q there and p 2^-lo below (NaN, both probabilities 0,
+            // counts as not below: q = 0)
+            const float aq = __builtin_fmaf(fq[j], LOG2E_F, -Aq), apl = __builtin_fmaf(fp[j], LOG2E_F, -Apl);
+            dl[j] = apl - aq;                                                      // d - lo
+            e[j] = __builtin_amdgcn_exp2f(fminf(aq, apl));
+            const bool below = dl[j] < 0.f;
+            pbf += below ? e[j] : 0.f;
+            nbf += below ? 0.f : e[j];
+            any |= __float_as_uint(dl[j]) < width_bits;                           // 0 <= d - lo < width
+        }
+        not_below += (double)nbf;
+        below_p += (double)pbf;
+        if (__ballot(any)) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                if (__float_as_uint(dl[j]) < width_bits) {
+                    const int b = (int)(dl[j] * inv_w);                            // <= BUDGET_FINE
+                    atomicAdd(&hq[b], e[j]);
+                    atomicAdd(&hp[b], __builtin_amdgcn_exp2f(__builtin_fmaf(fp[j], LOG2E_F, -Ap)));
+                }
+            }
+        }
+    });
+    lds_sync();
+    if (lane == 0) { hq[BUDGET_FINE - 1] += hq[BUDGET_FINE]; hp[BUDGET_FINE - 1] += hp[BUDGET_FINE]; }
+    lds_sync();
+    float inq = 0.f;
+    for (int e2 = lane; e2 < BUDGET_FINE; e2 += WAVE) inq += hq[e2];
+    pb = below_p * (double)scale_below;
+    qa = wave_sum(not_below) - wave_sum((double)inq);          // (wave total, on every lane)
+    qa = qa > 0.0 ? qa : 0.0;
+}
+
+// Exclusive sums over the lanes of a wave through LDS: for lane l the sum of `q` over the lanes
+// after it and of `p` over the lanes before it.  sq_ / sp_: 64 doubles each.
+__device__ __forceinline__ void budget_lane_sums(double q, double p, double *sq_, double *sp_, double &q_after,
+                                                 double &p_before, double &q_all, double &p_all)
 {
     const int lane = threadIdx.x;
-    sq_[lane] = Qb; sp_[lane] = Pbin;
     lds_sync();
-    // the q-mass of the bins from this lane's up, the p-mass of the bins below it
-    double Qsuf = 0.0, Ppre = 0.0, Ptot = 0.0;
+    sq_[lane] = q; sp_[lane] = p;
+    lds_sync();
+    q_after = 0.0; p_before = 0.0; q_all = 0.0; p_all = 0.0;
 #pragma unroll 4
-    for (int j = 0; j < BUDGET_BINS; ++j) {
+    for (int j = 0; j < WAVE; ++j) {
         const double qj = sq_[j], pj = sp_[j];
-        Qsuf += j >= lane ? qj : 0.0;
-        Ppre += j < lane ? pj : 0.0;
-        Ptot += pj;
+        q_after += j > lane ? qj : 0.0;
+        p_before += j < lane ? pj : 0.0;
+        q_all += qj;
+        p_all += pj;
     }
     lds_sync();
-    const float w = (hi - lo) / (float)BUDGET_BINS;
-    const float edge = lo + w * (float)lane;            // lower edge of this lane's bin
-    const double Zedge = A_above + Qsuf + (B_below + Ppre) * (double)__builtin_amdgcn_exp2f(-edge);
-    const double Zhi = A_above + (B_below + Ptot) * (double)__builtin_amdgcn_exp2f(-hi);
-    const int n_true = __popcll(__ballot(Zedge >= goal));
-    // Z(lambda -> 0) is all the mass that can be kept at all.  A budget at (or within rounding of)
-    // it is met by every lambda up to the smallest ratio, which is the answer; Z is flat there,
-    // so the bracket search would be deciding on rounding noise.
-    const double Zmax = A_above + lane_value_d(Qsuf, 0);
-    if (pass == 0 && (n_true == 0 || goal >= Zmax * (1.0 - 1e-6))) {
-        lambda = (double)__builtin_amdgcn_exp2f(dmin);
-        return true;
+}
+
+// What a sweep found.  `goal` is the value Z must reach (abar, or abar times the number of rows when
+// the masses are sums over a batch).
+struct BudgetFound {
+    int where;              // -1: crossing below lo, 0: inside (bin_lo .. bin_lo + bin_w), +1: above hi
+    float bin_lo, bin_w;
+    double lambda;          // closed form on the crossing bin (where == 0) or beyond the bracket (where == +1)
+    double bin_q;           // q-mass of the tokens inside the crossing bin
+};
+
+// Lane l brings the masses of NB consecutive bins (bins l NB .. l NB + NB - 1 of width w from lo).
+template <int NB>
+__device__ __forceinline__ BudgetFound budget_scan(double goal, double A_above, double B_below, const double (&q)[NB],
+                                                   const double (&p)[NB], float lo, float w, double *sq_, double *sp_)
+{
+    const int lane = threadIdx.x;
+    double tq = 0.0, tp = 0.0;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) { tq += q[j]; tp += p[j]; }
+    double q_after, p_before, q_all, p_all;
+    budget_lane_sums(tq, tp, sq_, sp_, q_after, p_before, q_all, p_all);
+    // Z at the lower edge of every bin: the q-mass from this bin up, the p-mass of the bins below it
+    double qsuf[NB], ppre[NB];
+    int n_true = 0;
+    {
+        double qs = q_after + tq, pp = p_before;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            qsuf[j] = qs; ppre[j] = pp;
+            const float edge = lo + w * (float)(lane * NB + j);
+            const double z = A_above + qs + (B_below + pp) * (double)__builtin_amdgcn_exp2f(-edge);
+            n_true += __popcll(__ballot(z >= goal));
+            qs -= q[j];
+            pp += p[j];
+        }
     }
-    if (pass == 0 && Zhi >= goal) {
-        lambda = (B_below + Ptot) / (goal - A_above);   // beyond 2^64: every ratio is below lambda
-        return true;
+    BudgetFound r;
+    const float hi = lo + w * (float)(WAVE * NB);
+    const double z_hi = A_above + (B_below + p_all) * (double)__builtin_amdgcn_exp2f(-hi);
+    r.bin_lo = lo; r.bin_w = w; r.bin_q = 0.0; r.lambda = 0.0;
+    if (n_true == 0) { r.where = -1; return r; }
+    if (z_hi >= goal) {
+        r.where = 1;
+        r.lambda = (B_below + p_all) / (goal - A_above);         // every ratio up to hi is below lambda
+        return r;
     }
-    int bstar = n_true > 0 ? n_true - 1 : 0;
-    bstar = bstar < BUDGET_BINS - 1 ? bstar : BUDGET_BINS - 1;
-    // masses as seen by lane bstar, made wave-uniform
-    const double Qs = lane_value_d(Qsuf, bstar), Pp = lane_value_d(Ppre, bstar);
-    const double Qself = lane_value_d(Qb, bstar), Pself = lane_value_d(Pbin, bstar);
-    const float nlo = lo + w * (float)bstar;
-    lo = nlo;
-    hi = nlo + w;
-    if (pass == BUDGET_PASSES - 1) {
-        const double Aend = A_above + (Qs - Qself), Bend = B_below + Pp + Pself;
-        lambda = Bend / (goal - Aend);
-        const double l_lo = (double)__builtin_amdgcn_exp2f(nlo), l_hi = (double)__builtin_amdgcn_exp2f(nlo + w);
-        lambda = lambda < l_lo ? l_lo : (lambda > l_hi ? l_hi : lambda);
-        return true;
+    const int g = n_true - 1;                                    // Z(edge g) >= goal > Z(edge g + 1)
+    const int owner = g / NB, jj = g - owner * NB;
+    double a_end = 0.0, b_end = 0.0, bq = 0.0;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        if (j == jj) { a_end = A_above + qsuf[j] - q[j]; b_end = B_below + ppre[j] + p[j]; bq = q[j]; }
     }
-    return false;
+    a_end = lane_value_d(a_end, owner); b_end = lane_value_d(b_end, owner); bq = lane_value_d(bq, owner);
+    r.where = 0;
+    r.bin_lo = lo + w * (float)g;
+    r.bin_q = bq;
+    double lambda = b_end / (goal - a_end);
+    const double l_lo = (double)__builtin_amdgcn_exp2f(r.bin_lo), l_hi = (double)__builtin_amdgcn_exp2f(r.bin_lo + w);
+    r.lambda = lambda < l_lo ? l_lo : (lambda > l_hi ? l_hi : lambda);
+    return r;
+}
+
+// After the first sweep: Z(lambda -> 0) is all the mass that can be kept at all.  A budget at (or
+// within rounding of) it is met by every lambda up to the smallest ratio, which is the answer; Z is
+// flat there, so a bracket search would be deciding on rounding noise: BUDGET_KEEP_ALL.  Otherwise
+// the bracket for the exact sweeps: the coarse bin of the approximate crossing and one bin on
+// either side (BUDGET_SEARCH).
+enum { BUDGET_SEARCH = 0, BUDGET_DONE = 1, BUDGET_KEEP_ALL = 2 };
+__device__ __forceinline__ int budget_after_coarse(double goal, const double (&q)[BUDGET_CPL], double *sq_, double *sp_,
+                                                   float &lo, float &hi)
+{
+    const int lane = threadIdx.x;
+    double p[BUDGET_CPL];
+#pragma unroll
+    for (int j = 0; j < BUDGET_CPL; ++j) {
+        const float mid = -BUDGET_CRANGE + BUDGET_COARSE_W * ((float)(lane * BUDGET_CPL + j) + 0.5f);
+        p[j] = q[j] * (double)__builtin_amdgcn_exp2f(mid);
+    }
+    double tq = 0.0;
+#pragma unroll
+    for (int j = 0; j < BUDGET_CPL; ++j) tq += q[j];
+    const double zmax = wave_sum(tq);
+    if (goal >= zmax * (1.0 - 1e-6)) return BUDGET_KEEP_ALL;
+    const BudgetFound f = budget_scan<BUDGET_CPL>(goal, 0.0, 0.0, q, p, -BUDGET_CRANGE, BUDGET_COARSE_W, sq_, sp_);
+    float centre = f.bin_lo;                                      // where == 0
+    if (f.where < 0) centre = -BUDGET_CRANGE;
+    if (f.where > 0) centre = BUDGET_CRANGE - BUDGET_COARSE_W;
+    lo = centre - BUDGET_COARSE_W;
+    hi = centre + 2.f * BUDGET_COARSE_W;
+    if (lo < -BUDGET_CRANGE) lo = -BUDGET_RANGE;                  // the first and the last bin reach out to the range
+    if (hi > BUDGET_CRANGE) hi = BUDGET_RANGE;
+    return BUDGET_SEARCH;
+}
+
+// After an exact sweep of [lo, hi): BUDGET_DONE (lambda set), BUDGET_KEEP_ALL (the crossing lies
+// below every ratio of the range), or BUDGET_SEARCH with the next bracket.
+// eps: the error of Z that is negligible (absolute); last: no further sweep is allowed.
+__device__ __forceinline__ int budget_after_fine(const BudgetFound &f, double eps, bool last, float &lo, float &hi,
+                                                 double &lambda)
+{
+    const float width = hi - lo;
+    if (f.where == 0) {
+        // tokens inside the crossing bin are priced as if they lay below lambda: off by at most
+        // their q-mass times (2^bin width - 1)
+        const double err = f.bin_q * ((double)__builtin_amdgcn_exp2f(f.bin_w) - 1.0);
+        lambda = f.lambda;
+        if (err <= eps || f.bin_w < 1e-6f || last) return BUDGET_DONE;
+        lo = f.bin_lo;
+        hi = f.bin_lo + f.bin_w;
+        return BUDGET_SEARCH;
+    }
+    if (f.where > 0) {
+        lambda = f.lambda;
+        if (hi >= BUDGET_RANGE || last) return BUDGET_DONE;       // beyond 2^64: every ratio is below lambda
+        lo = hi;
+        hi = fminf(hi + 8.f * width, BUDGET_RANGE);
+        return BUDGET_SEARCH;
+    }
+    if (lo <= -BUDGET_RANGE) return BUDGET_KEEP_ALL;
+    lambda = (double)__builtin_amdgcn_exp2f(lo);
+    if (last) return BUDGET_DONE;
+    hi = lo;
+    lo = fmaxf(lo - 8.f * width, -BUDGET_RANGE);
+    return BUDGET_SEARCH;
 }
 
 template <class ET>
-__global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
+__global__ __launch_bounds__(64, 6) void budget_kernel(BudgetArgs A)
 {
-    __shared__ double hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
-    __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
+    __shared__ uint32_t hist[2 * (BUDGET_COARSE + 1)];            // coarse bins; later the fine q / p bins
+    __shared__ double sq_[WAVE], sp_[WAVE];
+    float *const hq = (float *)hist, *const hp = hq + BUDGET_FINE + 1;
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     const float NaN = __uint_as_float(0x7fc00000u);
@@ -392,32 +508,41 @@ __global__ __launch_bounds__(64, 4) void budget_kernel(BudgetArgs A)
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
     const float Aq = (float)(A.lse_q[t] * LOG2E_D);
     const float Ap = (float)(A.lse_p[t] * LOG2E_D);
+    const double goal = (double)abar_f;
+    const double eps = goal * (double)A.eps_rel;
+
+    budget_coarse_sweep<ET>(rowq, rowp, A.V, Aq, Ap, hist);
+    double cq[BUDGET_CPL];
+#pragma unroll
+    for (int j = 0; j < BUDGET_CPL; ++j) {
+        const int b = 1 + lane * BUDGET_CPL + j;                  // (entry 0 holds what no lambda keeps)
+        cq[j] = ((double)hist[2 * b] + (double)hist[2 * b + 1]) / BUDGET_FIX31;
+    }
     float lo = -BUDGET_RANGE, hi = BUDGET_RANGE;
     double lambda = 0.0;
-    float dmin = __uint_as_float(0x7f800000u);
-    for (int pass = 0; pass < BUDGET_PASSES; ++pass) {
+    int state = budget_after_coarse(goal, cq, sq_, sp_, lo, hi);
+    for (int sweep = 1; sweep < BUDGET_MAX_SWEEPS && state == BUDGET_SEARCH; ++sweep) {
         double qa, pb;
-        if (pass == 0) budget_sweep<ET, true>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
-        else budget_sweep<ET, false>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
-        const double A_above = wave_sum(qa), B_below = wave_sum(pb);
-        // lane b owns bin b
-        double uq, up;
-        budget_bin_sums(hq, hp, pass == 0, uq, up);
-        const float dmin_w = pass == 0 ? -uniform_f(wave_max(-dmin)) : 0.f;
-        if (budget_step((double)abar_f, A_above, B_below, uq, up, lo, hi,
-                        pass, dmin_w, sq_, sp_, lambda))
-            break;
+        budget_fine_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb);
+        const double A_above = qa, B_below = wave_sum(pb);
+        double fq[BUDGET_FPL], fp[BUDGET_FPL];
+#pragma unroll
+        for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] = (double)hq[lane * BUDGET_FPL + j]; fp[j] = (double)hp[lane * BUDGET_FPL + j]; }
+        const BudgetFound f = budget_scan<BUDGET_FPL>(goal, A_above, B_below, fq, fp, lo, (hi - lo) / (float)BUDGET_FINE, sq_, sp_);
+        state = budget_after_fine(f, eps, sweep == BUDGET_MAX_SWEEPS - 1, lo, hi, lambda);
     }
+    if (state == BUDGET_KEEP_ALL) lambda = (double)__builtin_amdgcn_exp2f(budget_min_ratio<ET>(rowq, rowp, A.V, Aq, Ap));
     if (lane == 0) A.lambda_out[t] = (float)lambda;
 }
 
 // The same search for one lambda of a whole batch, mean_t Z_t(lambda) = abar: the bins of all rows are
-// summed in device memory (64-bit fixed point, 2^-32 units, so the sums are order-independent), a
-// one-wave kernel narrows the bracket between the sweeps, and nothing goes through the host.
+// summed in device memory (64-bit fixed point, so the sums are order-independent), a one-wave kernel
+// between the sweeps finds the next bracket, and nothing goes through the host.
 __global__ void budget_batch_init_kernel(BudgetBatchState *S)
 {
     const int lane = threadIdx.x;
-    S->bq[lane] = 0; S->bp[lane] = 0;
+    for (int e = lane; e < BUDGET_COARSE; e += WAVE) S->coarse[e] = 0;
+    for (int e = lane; e < BUDGET_FINE; e += WAVE) { S->fq[e] = 0; S->fp[e] = 0; }
     if (lane == 0) {
         S->lo = -BUDGET_RANGE; S->hi = BUDGET_RANGE; S->done = 0; S->lambda = 0.0;
         S->n_rows = 0; S->above = 0; S->below = 0; S->dmin_ord = 0x7fffffff;
@@ -432,64 +557,114 @@ __device__ __forceinline__ int float_order_int(float f)
 }
 
 template <class ET>
-__global__ __launch_bounds__(64, 4) void budget_batch_pass_kernel(BudgetArgs A, BudgetBatchState *S, int pass)
+__global__ __launch_bounds__(64, 6) void budget_batch_coarse_kernel(BudgetArgs A, BudgetBatchState *S)
 {
-    __shared__ double hq[BUDGET_BINS * BUDGET_COPIES], hp[BUDGET_BINS * BUDGET_COPIES];
+    __shared__ uint32_t hist[2 * (BUDGET_COARSE + 1)];
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
-    if (S->done || A.rowflag[t] != ROW_OK) return;
+    if (A.rowflag[t] != ROW_OK) return;
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
-    const float Aq = (float)(A.lse_q[t] * LOG2E_D);
-    const float Ap = (float)(A.lse_p[t] * LOG2E_D);
-    const float lo = S->lo, hi = S->hi;
-    float dmin = __uint_as_float(0x7f800000u);
-    double qa, pb;
-    if (pass == 0) budget_sweep<ET, true>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
-    else budget_sweep<ET, false>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, dmin);
-    const double A_above = wave_sum(qa), B_below = wave_sum(pb);
-    double dq, dp;
-    budget_bin_sums(hq, hp, pass == 0, dq, dp);
-    const unsigned long long uq = (unsigned long long)(dq * 4294967296.0), up = (unsigned long long)(dp * 4294967296.0);
-    if (uq) atomicAdd(&S->bq[lane], uq);                    // 2^-32 units: integer sums, any order
-    if (up) atomicAdd(&S->bp[lane], up);
-    if (pass == 0) dmin = -uniform_f(wave_max(-dmin));
+    budget_coarse_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), hist);
+    for (int b = lane; b < BUDGET_COARSE; b += WAVE) {
+        const unsigned long long u = (unsigned long long)hist[2 * (b + 1)] + (unsigned long long)hist[2 * (b + 1) + 1];
+        if (u) atomicAdd(&S->coarse[b], u);                   // 2^-31 units: integer sums, any order
+    }
+    if (lane == 0) atomicAdd(&S->n_rows, 1ull);
+}
+
+__global__ __launch_bounds__(64) void budget_batch_after_coarse_kernel(BudgetBatchState *S, float target, float *out_lambda)
+{
+    __shared__ double sq_[WAVE], sp_[WAVE];
+    const int lane = threadIdx.x;
+    const unsigned long long n = S->n_rows;
+    double cq[BUDGET_CPL];
+#pragma unroll
+    for (int j = 0; j < BUDGET_CPL; ++j) cq[j] = (double)S->coarse[lane * BUDGET_CPL + j] / BUDGET_FIX31;
+    float lo = -BUDGET_RANGE, hi = BUDGET_RANGE;
+    int state = BUDGET_DONE;
+    if (n > 0) state = budget_after_coarse((double)target * (double)n, cq, sq_, sp_, lo, hi);
     if (lane == 0) {
-        atomicAdd(&S->above, (unsigned long long)(A_above * 4294967296.0));
-        atomicAdd(&S->below, (unsigned long long)(B_below * 4294967296.0));
-        if (pass == 0) {
-            atomicAdd(&S->n_rows, 1ull);
-            atomicMin(&S->dmin_ord, float_order_int(dmin));
+        S->lo = lo; S->hi = hi;
+        S->done = state;
+        if (n == 0) {                                       // no valid row
+            S->lambda = __longlong_as_double(0x7ff8000000000000LL);
+            *out_lambda = __uint_as_float(0x7fc00000u);
         }
     }
 }
 
-__global__ __launch_bounds__(64) void budget_batch_scan_kernel(BudgetBatchState *S, float target, int pass, float *out_lambda)
+// Only when the search ended with "every lambda up to the smallest ratio": that ratio, over all rows.
+template <class ET>
+__global__ __launch_bounds__(64, 6) void budget_batch_min_ratio_kernel(BudgetArgs A, BudgetBatchState *S)
 {
-    __shared__ double sq_[BUDGET_BINS], sp_[BUDGET_BINS];
-    const int lane = threadIdx.x;
-    if (S->done) return;
-    const double unit = 1.0 / 4294967296.0;
-    const unsigned long long n = S->n_rows;
-    const double Qb = (double)S->bq[lane] * unit, Pbin = (double)S->bp[lane] * unit;
-    const double A_above = (double)S->above * unit, B_below = (double)S->below * unit;
-    float lo = S->lo, hi = S->hi;
+    const int64_t t = blockIdx.x;
+    if (S->done != BUDGET_KEEP_ALL || A.rowflag[t] != ROW_OK) return;
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const float dmin = budget_min_ratio<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D));
+    if (threadIdx.x == 0) atomicMin(&S->dmin_ord, float_order_int(dmin));
+}
+
+__global__ void budget_batch_min_ratio_finish_kernel(BudgetBatchState *S, float *out_lambda)
+{
+    if (threadIdx.x != 0 || S->done != BUDGET_KEEP_ALL) return;
     const int o = S->dmin_ord;
     const float dmin = __int_as_float(o ^ ((o >> 31) & 0x7fffffff));
-    double lambda = 0.0;
-    bool done;
-    if (n == 0) {                                           // no valid row
-        lambda = __longlong_as_double(0x7ff8000000000000LL);
-        done = true;
-    } else {
-        done = budget_step((double)target * (double)n, A_above, B_below, Qb, Pbin, lo, hi, pass, dmin, sq_, sp_, lambda);
+    S->lambda = (double)__builtin_amdgcn_exp2f(dmin);
+    S->done = BUDGET_DONE;
+    *out_lambda = (float)S->lambda;
+}
+
+template <class ET>
+__global__ __launch_bounds__(64, 6) void budget_batch_fine_kernel(BudgetArgs A, BudgetBatchState *S)
+{
+    __shared__ float hq[BUDGET_FINE + 1], hp[BUDGET_FINE + 1];
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    if (S->done != BUDGET_SEARCH || A.rowflag[t] != ROW_OK) return;
+    const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
+    const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
+    double qa, pb;
+    budget_fine_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), S->lo, S->hi, hq, hp, qa, pb);
+    const double A_above = qa, B_below = wave_sum(pb);
+    for (int b = lane; b < BUDGET_FINE; b += WAVE) {
+        const unsigned long long uq = (unsigned long long)((double)hq[b] * 4294967296.0), up = (unsigned long long)((double)hp[b] * 4294967296.0);
+        if (uq) atomicAdd(&S->fq[b], uq);                    // 2^-32 units: integer sums, any order
+        if (up) atomicAdd(&S->fp[b], up);
     }
+    if (lane == 0) {
+        atomicAdd(&S->above, (unsigned long long)(A_above * 4294967296.0));
+        atomicAdd(&S->below, (unsigned long long)(B_below * 4294967296.0));
+    }
+}
+
+__global__ __launch_bounds__(64) void budget_batch_after_fine_kernel(BudgetBatchState *S, float target, float eps_rel, int last,
+                                                                     float *out_lambda)
+{
+    __shared__ double sq_[WAVE], sp_[WAVE];
+    const int lane = threadIdx.x;
+    if (S->done != BUDGET_SEARCH) return;
+    const double unit = 1.0 / 4294967296.0;
+    const double goal = (double)target * (double)S->n_rows;
+    double fq[BUDGET_FPL], fp[BUDGET_FPL];
+#pragma unroll
+    for (int j = 0; j < BUDGET_FPL; ++j) {
+        fq[j] = (double)S->fq[lane * BUDGET_FPL + j] * unit;
+        fp[j] = (double)S->fp[lane * BUDGET_FPL + j] * unit;
+    }
+    float lo = S->lo, hi = S->hi;
+    const BudgetFound f = budget_scan<BUDGET_FPL>(goal, (double)S->above * unit, (double)S->below * unit, fq, fp, lo,
+                                                  (hi - lo) / (float)BUDGET_FINE, sq_, sp_);
+    double lambda = 0.0;
+    const int state = budget_after_fine(f, goal * (double)eps_rel, last != 0, lo, hi, lambda);
     lds_sync();
-    S->bq[lane] = 0; S->bp[lane] = 0;                       // the next sweep starts from empty bins
+    for (int e = lane; e < BUDGET_FINE; e += WAVE) { S->fq[e] = 0; S->fp[e] = 0; }     // the next sweep starts from empty bins
     if (lane == 0) {
         S->above = 0; S->below = 0;
         S->lo = lo; S->hi = hi;
-        if (done) { S->done = 1; S->lambda = lambda; *out_lambda = (float)lambda; }
+        S->done = state;
+        if (state == BUDGET_DONE) { S->lambda = lambda; *out_lambda = (float)lambda; }
     }
 }
 
@@ -789,15 +964,27 @@ hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st)
 
 hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState *S, float *out_lambda, hipStream_t st)
 {
-    hipLaunchKernelGGL(budget_batch_init_kernel, dim3(1), dim3(WAVE), 0, st, S);
-    for (int pass = 0; pass < BUDGET_PASSES; ++pass) {
-        if (a.T > 0) {
-            const dim3 grid((unsigned)a.T), block(WAVE);
-            if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_pass_kernel<Bf16Elem>), grid, block, 0, st, a, S, pass);
-            else hipLaunchKernelGGL((budget_batch_pass_kernel<F32Elem>), grid, block, 0, st, a, S, pass);
-        }
-        hipLaunchKernelGGL(budget_batch_scan_kernel, dim3(1), dim3(WAVE), 0, st, S, a.target, pass, out_lambda);
+    const dim3 grid((unsigned)(a.T > 0 ? a.T : 1)), block(WAVE);
+    hipLaunchKernelGGL(budget_batch_init_kernel, dim3(1), block, 0, st, S);
+    if (a.T > 0) {
+        if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_coarse_kernel<Bf16Elem>), grid, block, 0, st, a, S);
+        else hipLaunchKernelGGL((budget_batch_coarse_kernel<F32Elem>), grid, block, 0, st, a, S);
     }
+    hipLaunchKernelGGL(budget_batch_after_coarse_kernel, dim3(1), block, 0, st, S, a.target, out_lambda);
+    // the exact sweeps: as many launches as the search may need; once it has finished the rest return at once
+    for (int sweep = 1; sweep < BUDGET_MAX_SWEEPS; ++sweep) {
+        if (a.T > 0) {
+            if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_fine_kernel<Bf16Elem>), grid, block, 0, st, a, S);
+            else hipLaunchKernelGGL((budget_batch_fine_kernel<F32Elem>), grid, block, 0, st, a, S);
+        }
+        hipLaunchKernelGGL(budget_batch_after_fine_kernel, dim3(1), block, 0, st, S, a.target, a.eps_rel,
+                           sweep == BUDGET_MAX_SWEEPS - 1 ? 1 : 0, out_lambda);
+    }
+    if (a.T > 0) {
+        if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_min_ratio_kernel<Bf16Elem>), grid, block, 0, st, a, S);
+        else hipLaunchKernelGGL((budget_batch_min_ratio_kernel<F32Elem>), grid, block, 0, st, a, S);
+    }
+    hipLaunchKernelGGL(budget_batch_min_ratio_finish_kernel, dim3(1), block, 0, st, S, out_lambda);
     return hipGetLastError();
 }
 
