@@ -61,7 +61,12 @@ typedef enum jp_status {
     JP_ERR_TOO_LARGE = 8        /* jp_obrs_forward_static only: T > JP_STATIC_MAX_T    */
 } jp_status;
 
-typedef enum jp_dtype { JP_F32 = 0, JP_BF16 = 1 } jp_dtype;
+/* Element type of a logit tensor.  The argument is a plain 32-bit integer on both sides of the
+ * boundary, so a value outside the list is an error the library reports (JP_ERR_UNSUPPORTED) and not an
+ * out-of-range enumeration value, which a C++ callee could not even inspect without undefined
+ * behaviour.  jp_tail_rule below is declared the same way for the same reason. */
+typedef int32_t jp_dtype;
+enum { JP_F32 = 0, JP_BF16 = 1 };
 
 enum {
     JP_FLAG_EXACT_Z = 1,        /* also compute Z over the whole vocabulary (second sweep)  */
@@ -240,7 +245,8 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
  * are inputs here).  JP_FLAG_EXACT_Z and JP_FLAG_DISTILL_KL need the actor row: JP_ERR_UNSUPPORTED.
  * Workspace: jp_obrs_workspace_bytes.
  */
-typedef enum jp_tail_rule { JP_TAIL_DROP = 0, JP_TAIL_KTH = 1, JP_TAIL_REST = 2 } jp_tail_rule;
+typedef int32_t jp_tail_rule;
+enum { JP_TAIL_DROP = 0, JP_TAIL_KTH = 1, JP_TAIL_REST = 2 };
 jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V, int64_t row_stride,
                                  jp_dtype dt, const int32_t *actor_topk_ids,
                                  const float *actor_topk_logprob, const float *actor_logprob_x,
@@ -364,7 +370,8 @@ jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logi
                                void *grad_actor, int64_t grad_row_stride, jp_dtype grad_dt,
                                const void *workspace, size_t workspace_bytes, void *stream);
 
-const char *jp_status_string(jp_status s);
+/* Text for a status code (a static string; any other integer gives "unknown status"). */
+const char *jp_status_string(int32_t status);
 
 /* ABI version of this header (bumped on incompatible change). */
 int jp_obrs_abi_version(void);

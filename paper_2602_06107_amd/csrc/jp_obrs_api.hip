@@ -657,9 +657,9 @@ jp_status jp_obrs_distill_grad(const void *actor_logits, const void *policy_logi
     return JP_OK;
 }
 
-const char *jp_status_string(jp_status s)
+const char *jp_status_string(int32_t status)
 {
-    switch (s) {
+    switch (status) {
     case JP_OK: return "ok";
     case JP_ERR_NULL: return "required pointer is NULL";
     case JP_ERR_SHAPE: return "invalid shape";
