@@ -73,9 +73,13 @@ enum {
     JP_FLAG_TOPK_LOGPROBS = 2,  /* also write log-probabilities of the two top-k lists      */
     JP_FLAG_ALPHA_EXPECTED = 4, /* alpha_hat := mean_t a_t instead of accepted/proposed     */
     JP_FLAG_DISTILL_KL = 8,     /* also compute the per-token distillation term KL(p || q)   */
-    JP_FLAG_W_VOCAB_MAJOR = 16  /* jp_obrs_forward_lmhead only: W_* are [V, d] (one row per token
+    JP_FLAG_W_VOCAB_MAJOR = 16, /* jp_obrs_forward_lmhead only: W_* are [V, d] (one row per token
                                    of the vocabulary, the layout of an output embedding) instead
                                    of [d, V]; no transpose is then needed                     */
+    JP_FLAG_ONE_WAVE_PER_ROW = 32 /* never split a row over several wavefronts (the library does
+                                   so by itself for small batches, T <= 1792, in the two-tensor
+                                   form without JP_FLAG_DISTILL_KL; the index lists are the same
+                                   either way, floats agree to rounding of the log-sum-exp)   */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */

@@ -91,7 +91,7 @@ __device__ __forceinline__ int select_top_keys(typename KT::Key *buf, int cnt, i
                                                int early_limit, typename KT::Key &prefix_out)
 {
     using Key = typename KT::Key;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
     lds_sync();
     Key kk[NS];
 #pragma unroll
@@ -185,9 +185,17 @@ __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, boo
 // the running row state (exponent reference and sum of both rows, sampled-token logits, the two
 // top-k lists so far with both logits of every entry) is read from / written to a per-row record,
 // and only the launch of the last chunk runs the union / normaliser / acceptance step.
-template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false>
-__global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
+//
+// W > 1 gives a row to W wavefronts of one workgroup (for batches too small to fill the chip with
+// one wave per row, where a single wave's instruction stream, not the memory system, sets the
+// time of a row): wave w sweeps the w-th of W contiguous runs of chunks with descriptor buffers of
+// its own and keeps its best C / W descriptors per tensor; then the sums and the surviving
+// descriptors of all waves are put together in wave 0 (in wave order, which is chunk order, so
+// ties still resolve towards the smaller id), and wave 0 alone runs the rest exactly as for W = 1.
+template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false, int W = 1>
+__global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
+    static_assert(W == 1 || (!CARRY && !STORED), "rows are only split in the two-tensor form");
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
     constexpr int C = (KC >= 256 ? 3 : 4) * KC;   // descriptor buffer capacity per tensor
@@ -196,6 +204,8 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     constexpr int R = E / WAVE;
     using SO = SortOf<ET>;
     using SK = typename SO::SortKey;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
 
     // One LDS pool, used twice: during the sweep it holds the two descriptor buffers; once the
     // surviving descriptors sit in registers it holds the element candidates of the expansion.
@@ -206,7 +216,13 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     constexpr int POOL_BYTES0 = DESC_BYTES > CAND_BYTES ? DESC_BYTES : CAND_BYTES;
     constexpr int POOL_BYTES = ((POOL_BYTES0 > UNION_BYTES ? POOL_BYTES0 : UNION_BYTES) + 15) / 16 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char pool[POOL_BYTES];
-    Key *const s_desc0 = (Key *)pool;
+    // split rows: descriptor buffers of waves 1 .. W-1, and what every wave hands to wave 0
+    static_assert(W == 1 || W * KC <= C, "C / W descriptors per wave must hold the k best");
+    __shared__ Key s_more[W > 1 ? (W - 1) * 2 * C : 1];
+    __shared__ double s_part[W > 1 ? W : 1][3];                     // sums of actor / policy, distillation sum
+    __shared__ float s_pref[W > 1 ? W : 1][2];                      // their exponent references
+    __shared__ int s_pcnt[W > 1 ? W : 1][2];                        // descriptors kept
+    Key *const s_desc0 = (W > 1 && wv > 0) ? s_more + (size_t)(wv - 1) * 2 * C : (Key *)pool;
     Key *const s_desc1 = s_desc0 + C;
     SK *const s_key = (SK *)pool;                                   // candidate sort keys
     uint32_t *const s_cid = (uint32_t *)(pool + E * sizeof(SK));    // candidate token ids
@@ -218,7 +234,6 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     float *const l_a[2] = {(float *)(list0 + KC), (float *)pool + KC};
     float *const l_b[2] = {(float *)(list0 + 2 * KC), (float *)pool + 2 * KC};
 
-    const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     const int k = A.k;
     const int64_t V = A.V;
@@ -233,6 +248,7 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     uint32_t *const st_id0 = (uint32_t *)(state + sizeof(CarryHeader));     // [2][3][KC] words
     if (x < 0 || x >= V_total) {          // padding row, or a sampled id outside the vocabulary
         if (carry_out) return;            // reported by the launch of the last chunk
+        if (W > 1 && wv > 0) return;
         const bool pad = x < 0;
         const float fill = pad ? 0.f : NaN;
         if (lane == 0) {
@@ -310,14 +326,17 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
     };
 
     // ---- streaming sweep: iterations in which every lane owns a full 16-byte chunk ----------
-    if (nit > 0) {
+    // (iterations [it_lo, it_hi) belong to this wave: all of them when a wave has the whole row)
+    const uint32_t it_lo = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)wv / W) : 0u;
+    const uint32_t it_hi = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)(wv + 1) / W) : nit;
+    if (it_hi > it_lo) {
         // Two 16-byte loads per tensor stay in flight per lane: the loads for iterations it+2 and
         // it+3 are issued before iterations it and it+1 are consumed (indices clamp at the end).
-        const uint32_t last = nit - 1;
-        const uint32_t second = (last < 1u ? last : 1u) * WAVE + lane;
-        u32x4 wq0 = stream_load(vq + lane), wp0 = stream_load(vp + lane);
+        const uint32_t last = it_hi - 1;
+        const uint32_t second = (it_lo + 1u < last ? it_lo + 1u : last) * WAVE + lane;
+        u32x4 wq0 = stream_load(vq + it_lo * WAVE + lane), wp0 = stream_load(vp + it_lo * WAVE + lane);
         u32x4 wq1 = stream_load(vq + second), wp1 = stream_load(vp + second);
-        for (uint32_t it = 0; it < nit; it += 2) {
+        for (uint32_t it = it_lo; it < it_hi; it += 2) {
             const u32x4 cq0 = wq0, cp0 = wp0, cq1 = wq1, cp1 = wp1;
             const uint32_t n0 = (it + 2 < last ? it + 2 : last) * WAVE + lane;
             const uint32_t n1 = (it + 3 < last ? it + 3 : last) * WAVE + lane;
@@ -327,15 +346,15 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
             ET::unpack(cq0, fq);
             ET::unpack(cp0, fp);
             consume(fq, fp, it * WAVE + lane, true);
-            if (it + 1 < nit) {
+            if (it + 1 < it_hi) {
                 ET::unpack(cq1, fq);
                 ET::unpack(cp1, fp);
                 consume(fq, fp, (it + 1) * WAVE + lane, true);
             }
         }
     }
-    // ---- remainder: fewer than 64 chunks, the last of which may be ragged ------------------------
-    {
+    // ---- remainder: fewer than 64 chunks, the last of which may be ragged (the last wave's) -----
+    if (W == 1 || wv == W - 1) {
         const uint32_t c = nit * WAVE + lane;
         if (nit * WAVE < nchunks) {
             float fq[VEC], fp[VEC];
@@ -351,9 +370,46 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
         }
     }
 
+    double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
+    double Dp = DISTILL ? wave_sum((double)sp.d) : 0.0;
+    if constexpr (W > 1) {
+        // ---- split rows: every wave hands its sums and its best descriptors to wave 0 ------------
+        constexpr int LIM = C / W;                // >= KC >= k: the k best chunks of a run survive
+        Key unused;
+        const int n0 = uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, LIM, unused));
+        const int n1 = uniform_i(select_top_keys<KT, NS>(s_desc1, sp.cnt, k, false, LIM, unused));
+        if (lane == 0) {
+            s_part[wv][0] = Sq; s_part[wv][1] = Sp; s_part[wv][2] = Dp;
+            s_pref[wv][0] = sq.M2; s_pref[wv][1] = sp.M2;
+            s_pcnt[wv][0] = n0; s_pcnt[wv][1] = n1;
+        }
+        __syncthreads();
+        if (wv > 0) return;
+        int c0 = n0, c1 = n1;
+        float Mq = sq.M2, Mp = sp.M2;
+#pragma unroll
+        for (int w = 1; w < W; ++w) {
+            const Key *src0 = s_more + (size_t)(w - 1) * 2 * C, *src1 = src0 + C;
+            const int a0 = s_pcnt[w][0], a1 = s_pcnt[w][1];
+            for (int e = lane; e < a0; e += WAVE) s_desc0[c0 + e] = src0[e];
+            for (int e = lane; e < a1; e += WAVE) s_desc1[c1 + e] = src1[e];
+            c0 += a0; c1 += a1;
+            Mq = fmaxf(Mq, s_pref[w][0]); Mp = fmaxf(Mp, s_pref[w][1]);
+        }
+        sq.cnt = c0; sp.cnt = c1;
+        // sums on the common (largest) exponent reference, as the lanes of one wave have them
+        Sq = 0.0; Sp = 0.0; Dp = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const double fq2 = (double)__builtin_amdgcn_exp2f(s_pref[w][0] - Mq);
+            const double fp2 = (double)__builtin_amdgcn_exp2f(s_pref[w][1] - Mp);
+            Sq += s_part[w][0] * fq2; Sp += s_part[w][1] * fp2; Dp += s_part[w][2] * fp2;
+        }
+        sq.M2 = Mq; sp.M2 = Mp;
+        lds_sync();
+    }
+
     // ---- log-sum-exp of both rows (log2 domain until the last step) -----------------------------
-    const double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
-    const double Dp = DISTILL ? wave_sum((double)sp.d) : 0.0;
     // stored form: the actor side arrives as log-probabilities, i.e. logits whose log-sum-exp is 0
     const double lse_q = STORED ? 0.0 : ((double)sq.M2 + log2_of_sum(Sq)) * LN2_D;
     const double lse_p = ((double)sp.M2 + log2_of_sum(Sp)) * LN2_D;
@@ -722,7 +778,8 @@ __global__ __launch_bounds__(64, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 :
 
 // ---- launchers ------------------------------------------------------------------------------
 
-template <class ET, class KT>
+// SPLIT: also instantiate the forms that give a row to two or four waves (a.waves).
+template <class ET, class KT, bool SPLIT>
 static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T), block(WAVE);
@@ -730,11 +787,28 @@ static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
         if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, true>), grid, block, 0, st, a);
         else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, true>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, true>), grid, block, 0, st, a);
-    } else {
-        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false>), grid, block, 0, st, a);
-        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false>), grid, block, 0, st, a);
+        return hipGetLastError();
     }
+    if constexpr (SPLIT) {
+        // four waves need room for 4 k descriptors in wave 0's buffer: not at k > 128
+        const int w = a.waves >= 4 && a.k <= 128 ? 4 : (a.waves >= 2 ? 2 : 1);
+        if (w == 4) {
+            const dim3 b4(4 * WAVE);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, false, 4>), grid, b4, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, false, 4>), grid, b4, 0, st, a);
+            return hipGetLastError();
+        }
+        if (w == 2) {
+            const dim3 b2(2 * WAVE);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, false, 2>), grid, b2, 0, st, a);
+            else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, false, 2>), grid, b2, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false, false, 2>), grid, b2, 0, st, a);
+            return hipGetLastError();
+        }
+    }
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
@@ -769,10 +843,10 @@ hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st)
     if (a.T <= 0) return hipSuccess;
     if (dtype == JP_BF16) {
         const int64_t nchunks = (a.V + Bf16Elem::VEC - 1) / Bf16Elem::VEC;
-        if (nchunks <= 65535) return launch_rows_k<Bf16Elem, Key32>(a, st);
-        return launch_rows_k<Bf16Elem, Key64>(a, st);
+        if (nchunks <= 65535) return launch_rows_k<Bf16Elem, Key32, true>(a, st);
+        return launch_rows_k<Bf16Elem, Key64, false>(a, st);
     }
-    return launch_rows_k<F32Elem, Key64>(a, st);
+    return launch_rows_k<F32Elem, Key64, true>(a, st);
 }
 
 template <class ET, class KT>

@@ -20,6 +20,7 @@ JP_K_MAX = 256
 JP_F32, JP_BF16 = 0, 1
 JP_FLAG_EXACT_Z, JP_FLAG_TOPK_LOGPROBS, JP_FLAG_ALPHA_EXPECTED, JP_FLAG_DISTILL_KL = 1, 2, 4, 8
 JP_FLAG_W_VOCAB_MAJOR = 16
+JP_FLAG_ONE_WAVE_PER_ROW = 32
 JP_DATA_ERR_ID_RANGE, JP_DATA_ERR_NONFINITE, JP_DATA_ERR_EMPTY = 1, 2, 4
 JP_TAIL_DROP, JP_TAIL_KTH, JP_TAIL_REST = 0, 1, 2
 JP_F_TRUNCATE, JP_F_IDENTITY, JP_F_BAND = 0, 1, 2
