@@ -78,8 +78,8 @@ enum {
                                    of [d, V]; no transpose is then needed                     */
     JP_FLAG_ONE_WAVE_PER_ROW = 32 /* never split a row over several wavefronts (the library does
                                    so by itself for small batches, T <= 1792, in the two-tensor
-                                   form without JP_FLAG_DISTILL_KL; the index lists are the same
-                                   either way, floats agree to rounding of the log-sum-exp)   */
+                                   form; the index lists are the same either way, floats agree
+                                   to rounding of the log-sum-exp)                            */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */

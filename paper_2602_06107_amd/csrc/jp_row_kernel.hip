@@ -779,37 +779,37 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
 // ---- launchers ------------------------------------------------------------------------------
 
 // SPLIT: also instantiate the forms that give a row to two or four waves (a.waves).
-template <class ET, class KT, bool SPLIT>
-static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
+template <class ET, class KT, bool SPLIT, bool DISTILL>
+static hipError_t launch_rows_kd(const RowArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.distill) {
-        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, true>), grid, block, 0, st, a);
-        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, true>), grid, block, 0, st, a);
-        return hipGetLastError();
-    }
     if constexpr (SPLIT) {
         // four waves need room for 4 k descriptors in wave 0's buffer: not at k > 128
         const int w = a.waves >= 4 && a.k <= 128 ? 4 : (a.waves >= 2 ? 2 : 1);
         if (w == 4) {
             const dim3 b4(4 * WAVE);
-            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, false, 4>), grid, b4, 0, st, a);
-            else hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, false, 4>), grid, b4, 0, st, a);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, DISTILL, false, 4>), grid, b4, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, DISTILL, false, 4>), grid, b4, 0, st, a);
             return hipGetLastError();
         }
         if (w == 2) {
             const dim3 b2(2 * WAVE);
-            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, false, 2>), grid, b2, 0, st, a);
-            else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, false, 2>), grid, b2, 0, st, a);
-            else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false, false, 2>), grid, b2, 0, st, a);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, DISTILL, false, 2>), grid, b2, 0, st, a);
+            else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, DISTILL, false, 2>), grid, b2, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, DISTILL, false, 2>), grid, b2, 0, st, a);
             return hipGetLastError();
         }
     }
-    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false>), grid, block, 0, st, a);
-    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false>), grid, block, 0, st, a);
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, DISTILL>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, DISTILL>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, DISTILL>), grid, block, 0, st, a);
     return hipGetLastError();
+}
+
+template <class ET, class KT, bool SPLIT>
+static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
+{
+    return a.distill ? launch_rows_kd<ET, KT, SPLIT, true>(a, st) : launch_rows_kd<ET, KT, SPLIT, false>(a, st);
 }
 
 hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st)

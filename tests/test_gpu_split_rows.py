@@ -1,5 +1,5 @@
 """Rows split over two or four wavefronts (what the library does by itself for small batches of
-long rows, in the two-tensor form without the distillation term) against the oracle and against
+long rows in the two-tensor form) against the oracle and against
 the one-wave-per-row form of the same call (JP_FLAG_ONE_WAVE_PER_ROW): index lists and union sizes
 must be identical, floats agree to the tolerance of the dtype."""
 import numpy as np
@@ -14,7 +14,8 @@ if torch.cuda.is_available():
     import parity_util as pu
 
 DEV = "cuda"
-FLAGS = 1 | 2                       # exact Z + top-k log-probabilities (no distillation term: rows are split)
+FLAGS = 1 | 2                       # exact Z + top-k log-probabilities
+KL = 8                              # + the distillation term (another instantiation of the kernel)
 ONE = 32                            # JP_FLAG_ONE_WAVE_PER_ROW
 
 
@@ -33,9 +34,11 @@ def _same_as_one_wave(w, buf, flags=FLAGS):
     # a token whose uniform sits within rounding of its acceptance probability may take either mask
     # value; the batch factor kappa, and with it every weight, then differs between the two runs
     same_mask = np.array_equal(buf.mask.cpu().numpy(), ref.mask.cpu().numpy())
-    for name in ("accept_prob", "z_approx", "z_exact") + (("w_obrs", "rho") if same_mask else ()):
+    kl = ("distill_kl",) if flags & KL else ()
+    for name in ("accept_prob", "z_approx", "z_exact") + kl + (("w_obrs", "rho") if same_mask else ()):
         a, b = getattr(buf, name).float().cpu().numpy(), getattr(ref, name).float().cpu().numpy()
-        np.testing.assert_allclose(a, b, rtol=tol, atol=1e-30, equal_nan=True, err_msg=name)
+        np.testing.assert_allclose(a, b, rtol=tol, atol=tol if name == "distill_kl" else 1e-30, equal_nan=True,
+                                   err_msg=name)
     for name in ("logq", "logp", "logratio", "topk_actor_logq", "topk_policy_logp"):
         a, b = getattr(buf, name).float().cpu().numpy(), getattr(ref, name).float().cpu().numpy()
         fin = np.isfinite(a) & np.isfinite(b)
@@ -87,8 +90,9 @@ def test_random_case_split(seed):
     c = _case(seed)
     _say({n: (str(v) if n == "dtype" else v) for n, v in c.items()})
     w = _workload(c, seed)
-    buf, R, st = pu.check_all(w, FLAGS)
-    _same_as_one_wave(w, buf)
+    flags = FLAGS | (KL if seed % 2 else 0)
+    buf, R, st = pu.check_all(w, flags)
+    _same_as_one_wave(w, buf, flags)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
