@@ -172,7 +172,7 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
 //     instruction seldom meet in a bin, and few tokens fall into the bracket of the next sweep.
 //   * Every later sweep is exact: the mass outside the bracket [lo, hi) goes to per-lane sums (one
 //     exponential per token: p below the bracket, q above it), the tokens inside it to 256 fine bins
-//     (fp32 LDS atomics; the bins belong to this wave alone and the hardware takes the lanes of an
+//     (float64 LDS atomics; the bins belong to this wave alone and the hardware takes the lanes of an
 //     instruction in a fixed order, so the sums are reproducible).  If the crossing is not inside
 //     after all (a degenerate row), the bracket moves to that side and widens; if it is, the sweep
 //     ends with the closed form lambda = B / (abar - A) on the crossing bin, A the q-mass above it
@@ -290,11 +290,11 @@ __device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *
 // into the last bin).
 template <class ET>
 __device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
-                                                  float lo, float hi, float *hq, float *hp, double &qa, double &pb)
+                                                  float lo, float hi, double *hq, double *hp, double &qa, double &pb)
 {
     constexpr int VEC = ET::VEC;
     const int lane = threadIdx.x;
-    for (int e = lane; e < BUDGET_FINE + 1; e += WAVE) { hq[e] = 0.f; hp[e] = 0.f; }
+    for (int e = lane; e < BUDGET_FINE + 1; e += WAVE) { hq[e] = 0.0; hp[e] = 0.0; }
     lds_sync();
     const float width = hi - lo;
     const float inv_w = (float)BUDGET_FINE / width;
@@ -326,8 +326,10 @@ __device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *
             for (int j = 0; j < VEC; ++j) {
                 if (__float_as_uint(dl[j]) < width_bits) {
                     const int b = (int)(dl[j] * inv_w);                            // <= BUDGET_FINE
-                    atomicAdd(&hq[b], e[j]);
-                    atomicAdd(&hp[b], __builtin_amdgcn_exp2f(__builtin_fmaf(fp[j], LOG2E_F, -Ap)));
+                    // (float64 bins: thousands of equal terms, a row of tied logits, added to one
+                    // fp32 bin round the same way every time and drift by 1e-4 of the sum)
+                    atomicAdd(&hq[b], (double)e[j]);
+                    atomicAdd(&hp[b], (double)__builtin_amdgcn_exp2f(__builtin_fmaf(fp[j], LOG2E_F, -Ap)));
                 }
             }
         }
@@ -335,10 +337,10 @@ __device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *
     lds_sync();
     if (lane == 0) { hq[BUDGET_FINE - 1] += hq[BUDGET_FINE]; hp[BUDGET_FINE - 1] += hp[BUDGET_FINE]; }
     lds_sync();
-    float inq = 0.f;
+    double inq = 0.0;
     for (int e2 = lane; e2 < BUDGET_FINE; e2 += WAVE) inq += hq[e2];
     pb = below_p * (double)scale_below;
-    qa = wave_sum(not_below) - wave_sum((double)inq);          // (wave total, on every lane)
+    qa = wave_sum(not_below) - wave_sum(inq);          // (wave total, on every lane)
     qa = qa > 0.0 ? qa : 0.0;
 }
 
@@ -492,9 +494,10 @@ __device__ __forceinline__ int budget_after_fine(const BudgetFound &f, double ep
 template <class ET>
 __global__ __launch_bounds__(64, 6) void budget_kernel(BudgetArgs A)
 {
-    __shared__ uint32_t hist[2 * (BUDGET_COARSE + 1)];            // coarse bins; later the fine q / p bins
+    // coarse bins (2 x 513 32-bit words); later the fine q / p bins (2 x 257 doubles)
+    __shared__ __attribute__((aligned(8))) uint32_t hist[4 * (BUDGET_FINE + 1) > 2 * (BUDGET_COARSE + 1) ? 4 * (BUDGET_FINE + 1) : 2 * (BUDGET_COARSE + 1)];
     __shared__ double sq_[WAVE], sp_[WAVE];
-    float *const hq = (float *)hist, *const hp = hq + BUDGET_FINE + 1;
+    double *const hq = (double *)hist, *const hp = hq + BUDGET_FINE + 1;
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     const float NaN = __uint_as_float(0x7fc00000u);
@@ -527,7 +530,7 @@ __global__ __launch_bounds__(64, 6) void budget_kernel(BudgetArgs A)
         const double A_above = qa, B_below = wave_sum(pb);
         double fq[BUDGET_FPL], fp[BUDGET_FPL];
 #pragma unroll
-        for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] = (double)hq[lane * BUDGET_FPL + j]; fp[j] = (double)hp[lane * BUDGET_FPL + j]; }
+        for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] = hq[lane * BUDGET_FPL + j]; fp[j] = hp[lane * BUDGET_FPL + j]; }
         const BudgetFound f = budget_scan<BUDGET_FPL>(goal, A_above, B_below, fq, fp, lo, (hi - lo) / (float)BUDGET_FINE, sq_, sp_);
         state = budget_after_fine(f, eps, sweep == BUDGET_MAX_SWEEPS - 1, lo, hi, lambda);
     }
@@ -619,7 +622,7 @@ __global__ void budget_batch_min_ratio_finish_kernel(BudgetBatchState *S, float 
 template <class ET>
 __global__ __launch_bounds__(64, 6) void budget_batch_fine_kernel(BudgetArgs A, BudgetBatchState *S)
 {
-    __shared__ float hq[BUDGET_FINE + 1], hp[BUDGET_FINE + 1];
+    __shared__ double hq[BUDGET_FINE + 1], hp[BUDGET_FINE + 1];
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     if (S->done != BUDGET_SEARCH || A.rowflag[t] != ROW_OK) return;
@@ -629,7 +632,7 @@ __global__ __launch_bounds__(64, 6) void budget_batch_fine_kernel(BudgetArgs A, 
     budget_fine_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), S->lo, S->hi, hq, hp, qa, pb);
     const double A_above = qa, B_below = wave_sum(pb);
     for (int b = lane; b < BUDGET_FINE; b += WAVE) {
-        const unsigned long long uq = (unsigned long long)((double)hq[b] * 4294967296.0), up = (unsigned long long)((double)hp[b] * 4294967296.0);
+        const unsigned long long uq = (unsigned long long)(hq[b] * 4294967296.0), up = (unsigned long long)(hp[b] * 4294967296.0);
         if (uq) atomicAdd(&S->fq[b], uq);                    // 2^-32 units: integer sums, any order
         if (up) atomicAdd(&S->fp[b], up);
     }

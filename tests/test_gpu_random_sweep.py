@@ -74,7 +74,9 @@ def test_random_case_stored_actor_side(seed):
     stored_form.run_case(_workload(c, seed), rule, flags=2)
 
 
-@pytest.mark.parametrize("seed", range(64, 88))
+# 287 .. 660: fp32 logits rounded to multiples of 2, so a row has a handful of distinct ratios and
+# thousands of equal terms meet in one histogram bin (sums in fp32 drift there: the bins are float64)
+@pytest.mark.parametrize("seed", list(range(64, 88)) + [287, 380, 532, 589, 660])
 def test_random_case_budget(seed):
     """The same kind of case through jp_obrs_lambda_for_budget with a random budget per row, and
     through the per-batch solver with one random budget."""
