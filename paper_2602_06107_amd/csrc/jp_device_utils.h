@@ -19,6 +19,7 @@ constexpr double LN2_D = 0.69314718055994530942;
 // row sum stays below 2^64 * V, far inside fp32 range.
 constexpr float RESCALE_MARGIN2 = 64.0f;
 constexpr float M2_UNSET = -3.0e38f;
+constexpr int BLOCK_CHUNKS = 48;                       // chunk sums per lane between two folds of a two-level sum
 
 __device__ __forceinline__ float neg_inf() { return __uint_as_float(0xff800000u); }
 

@@ -37,12 +37,27 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
     const float Aq = (float)(A.lse_q[t] * LOG2E_D);
     const float Ap = (float)((A.lse_p[t] + log((double)A.lambda)) * LOG2E_D);
-    float s0 = 0.f, s1 = 0.f;
+    // Two-level sum per lane: a chunk is summed by itself, chunk sums go to `s`, and every
+    // BLOCK_CHUNKS chunks `s` is folded into `hi`.  No single accumulator then takes more than a
+    // few dozen additions, which matters for rows of tied logits: thousands of EQUAL terms added to
+    // one fp32 accumulator round the same way every time and drift by 1e-5 of the sum and more.
+    // (fp32 logits are held to 1e-5 and get the two levels; bf16 logits, held to 1e-3, keep two
+    // plain accumulators.)
+    constexpr bool TWO_LEVEL = ET::ESZ == 4;
+    float s = 0.f, s1 = 0.f, hi = 0.f;
+    int until_fold = BLOCK_CHUNKS;
     auto account = [&](const float (&fq)[VEC], const float (&fp)[VEC]) {
+        float a = 0.f, b = 0.f;
 #pragma unroll
         for (int j = 0; j < VEC; j += 2) {
-            s0 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j], LOG2E_F, -Aq), __builtin_fmaf(fp[j], LOG2E_F, -Ap)));
-            s1 += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j + 1], LOG2E_F, -Aq), __builtin_fmaf(fp[j + 1], LOG2E_F, -Ap)));
+            a += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j], LOG2E_F, -Aq), __builtin_fmaf(fp[j], LOG2E_F, -Ap)));
+            b += __builtin_amdgcn_exp2f(fminf(__builtin_fmaf(fq[j + 1], LOG2E_F, -Aq), __builtin_fmaf(fp[j + 1], LOG2E_F, -Ap)));
+        }
+        if constexpr (TWO_LEVEL) {
+            s += a + b;
+            if (--until_fold == 0) { hi += s; s = 0.f; until_fold = BLOCK_CHUNKS; }
+        } else {
+            s += a; s1 += b;
         }
     };
     const uint32_t nit = nfull / WAVE;                      // iterations in which every lane has a full chunk
@@ -81,7 +96,7 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
             account(fq, fp);
         }
     }
-    const double Z = wave_sum((double)s0 + (double)s1);
+    const double Z = wave_sum((double)hi + (double)s + (double)s1);
     if (lane == 0) A.zexact[t] = (float)Z;
 }
 
@@ -108,16 +123,23 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
     const int tail = (int)(V - (int64_t)nfull * VEC);
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
     const uint32_t nit = nfull / WAVE;
-    float M2 = M2_UNSET, mthr = -2.0e38f, s = 0.f;
+    constexpr bool TWO_LEVEL = ET::ESZ == 4;                        // (two-level sum as in zexact_kernel)
+    float M2 = M2_UNSET, mthr = -2.0e38f, s = 0.f, hi = 0.f;
+    int until_fold = BLOCK_CHUNKS;
     auto consume = [&](const float (&f)[VEC], bool valid) {
         const float m = max_of<VEC>(f);
         if (valid && m > mthr) {                                    // rare: move this lane's reference
             const float newM2 = m * LOG2E_F;
-            s *= __builtin_amdgcn_exp2f(M2 - newM2);
+            const float rescale = __builtin_amdgcn_exp2f(M2 - newM2);
+            s *= rescale;
+            if constexpr (TWO_LEVEL) hi *= rescale;
             M2 = newM2;
             mthr = m + RESCALE_MARGIN2 / LOG2E_F;
         }
         if (valid) s += sum_exp2<VEC>(f, M2);
+        if constexpr (TWO_LEVEL) {
+            if (--until_fold == 0) { hi += s; s = 0.f; until_fold = BLOCK_CHUNKS; }
+        }
     };
     if (nit > 0) {
         constexpr int D = 4;
@@ -151,7 +173,7 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
     }
     // combine the 64 (reference, sum) pairs: common reference = the largest, sums rescaled to it
     const float Mw = uniform_f(wave_max(M2));
-    const double S = wave_sum(M2 == M2_UNSET ? 0.0 : (double)(s * __builtin_amdgcn_exp2f(M2 - Mw)));
+    const double S = wave_sum(M2 == M2_UNSET ? 0.0 : ((double)hi + (double)s) * (double)__builtin_amdgcn_exp2f(M2 - Mw));
     const double lse = ((double)Mw + log2_of_sum(S)) * LN2_D;
     const double lp = (double)ET::load1(row, x) - lse;
     if (lane == 0) A.out[t] = isfinite(lse) ? (float)lp : __uint_as_float(0x7fc00000u);

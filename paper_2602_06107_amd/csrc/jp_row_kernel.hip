@@ -138,6 +138,7 @@ template <class Key> struct Stream {
     Key tauk;         // exact form of the same bound (keys below it are not inserted)
     int cnt;          // descriptors currently buffered
     float d;          // policy stream only: per-lane sum of 2^(lp*log2e - M2) * (lp - lq)
+    float hi, dhi;    // fp32 logits only: what `s` / `d` held at the last fold of the two-level sum
 };
 
 template <class KT, int C, int NS>
@@ -162,7 +163,7 @@ __device__ __forceinline__ void offer_chunk(Stream<typename KT::Key> &st, typena
 }
 
 // A chunk maximum above st.mthr moves the exponent reference of the stream.
-template <class Key>
+template <bool TWO_LEVEL, class Key>
 __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, bool pass)
 {
     const float wm = uniform_f(wave_max(pass ? cmax : neg_inf()));
@@ -170,6 +171,7 @@ __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, boo
     const float rescale = __builtin_amdgcn_exp2f(st.M2 - newM2);
     st.s *= rescale;
     st.d *= rescale;
+    if constexpr (TWO_LEVEL) { st.hi *= rescale; st.dhi *= rescale; }
     st.M2 = newM2;
     st.mthr = wm + RESCALE_MARGIN2 / LOG2E_F;
 }
@@ -277,8 +279,13 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
     const uint32_t nit = nfull / WAVE;
 
-    Stream<Key> sq{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
-    Stream<Key> sp{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0};
+    Stream<Key> sq{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0, 0.f, 0.f, 0.f};
+    Stream<Key> sp{0.f, M2_UNSET, -2.0e38f, neg_inf(), (Key)1, 0, 0.f, 0.f, 0.f};
+    // fp32 logits are held to 1e-5: the lane sums are then kept in two levels (chunk sums go to `s`,
+    // `s` is folded into `hi` every BLOCK_CHUNKS chunks), because thousands of EQUAL terms (a row of
+    // tied logits) added to one fp32 accumulator round the same way every time and drift by 1e-5
+    // of the sum.  bf16 logits are held to 1e-3 and keep the single accumulator (and its register).
+    constexpr bool TWO_LEVEL = ET::ESZ == 4;
     int nl_in[2] = {0, 0};                // entries of the carried top-k lists
     float xq_in = 0.f, xp_in = 0.f;
     int have_x = 0;
@@ -316,8 +323,8 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
             // a value above the margin of an exponent reference is also above the top-k bound
             const bool rq = pq && mq > sq.mthr, rp = pp && mp > sp.mthr;
             if (__ballot(rq || rp)) {
-                if (__ballot(rq)) raise_reference(sq, mq, pq);
-                if (__ballot(rp)) raise_reference(sp, mp, pp);
+                if (__ballot(rq)) raise_reference<TWO_LEVEL>(sq, mq, pq);
+                if (__ballot(rp)) raise_reference<TWO_LEVEL>(sp, mp, pp);
             }
         }
         if constexpr (!STORED) sq.s += sum_exp2<VEC>(fq, sq.M2);
@@ -351,6 +358,13 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
                 ET::unpack(cp1, fp);
                 consume(fq, fp, (it + 1) * WAVE + lane, true);
             }
+            if constexpr (TWO_LEVEL) {
+                if (((it - it_lo) / 2) % (BLOCK_CHUNKS / 2) == BLOCK_CHUNKS / 2 - 1) {
+                    sq.hi += sq.s; sq.s = 0.f;
+                    sp.hi += sp.s; sp.s = 0.f;
+                    if constexpr (DISTILL) { sp.dhi += sp.d; sp.d = 0.f; }
+                }
+            }
         }
     }
     // ---- remainder: fewer than 64 chunks, the last of which may be ragged (the last wave's) -----
@@ -370,8 +384,8 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
         }
     }
 
-    double Sq = wave_sum((double)sq.s), Sp = wave_sum((double)sp.s);
-    double Dp = DISTILL ? wave_sum((double)sp.d) : 0.0;
+    double Sq = wave_sum((double)sq.hi + (double)sq.s), Sp = wave_sum((double)sp.hi + (double)sp.s);
+    double Dp = DISTILL ? wave_sum((double)sp.dhi + (double)sp.d) : 0.0;
     if constexpr (W > 1) {
         // ---- split rows: every wave hands its sums and its best descriptors to wave 0 ------------
         constexpr int LIM = C / W;                // >= KC >= k: the k best chunks of a run survive
