@@ -18,15 +18,18 @@ namespace jp {
 // Exact normaliser (diagnostic): Z_t = sum_v min(q_v, p_v/lambda) = sum_v 2^min(aq_v, ap_v) with
 // aq = (lq - LSEq) log2e, ap = (lp - LSEp - ln lambda) log2e.  One wavefront per row.
 // =================================================================================================
-template <class ET>
-__global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
+// W > 1: a row goes to W wavefronts of one workgroup, each with a contiguous run of the sweep
+// iterations (small batches, where one wave per row leaves the chip idle); wave 0 adds the parts.
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W) void zexact_kernel(ZExactArgs A)
 {
     constexpr int VEC = ET::VEC;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
     const int64_t t = blockIdx.x;
     const uint8_t flag = A.rowflag[t];
     if (flag != ROW_OK) {
-        if (lane == 0) A.zexact[t] = (flag == ROW_PADDING) ? 0.f : __uint_as_float(0x7fc00000u);
+        if (threadIdx.x == 0) A.zexact[t] = (flag == ROW_PADDING) ? 0.f : __uint_as_float(0x7fc00000u);
         return;
     }
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
@@ -61,24 +64,26 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
         }
     };
     const uint32_t nit = nfull / WAVE;                      // iterations in which every lane has a full chunk
-    if (nit > 0) {
+    const uint32_t it_lo = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)wv / W) : 0u;
+    const uint32_t it_hi = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)(wv + 1) / W) : nit;
+    if (it_hi > it_lo) {
         constexpr int D = 3;                                // non-temporal loads in flight per tensor and lane
-        const uint32_t last = nit - 1;
+        const uint32_t last = it_hi - 1;
         u32x4 wq[D], wp[D];
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            const uint32_t n = ((uint32_t)d < last ? (uint32_t)d : last) * WAVE + lane;
+            const uint32_t n = (it_lo + (uint32_t)d < last ? it_lo + (uint32_t)d : last) * WAVE + lane;
             wq[d] = stream_load(as_global_vec(rowq) + n);
             wp[d] = stream_load(as_global_vec(rowp) + n);
         }
-        for (uint32_t it = 0; it < nit; it += D) {
+        for (uint32_t it = it_lo; it < it_hi; it += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const u32x4 cq = wq[d], cp = wp[d];
                 const uint32_t n = (it + D + d < last ? it + D + d : last) * WAVE + lane;
                 wq[d] = stream_load(as_global_vec(rowq) + n);
                 wp[d] = stream_load(as_global_vec(rowp) + n);
-                if (d == 0 || it + d < nit) {
+                if (d == 0 || it + d < it_hi) {
                     float fq[VEC], fp[VEC];
                     ET::unpack(cq, fq);
                     ET::unpack(cp, fp);
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
             }
         }
     }
-    {
+    if (W == 1 || wv == W - 1) {                            // the remainder belongs to the last wave
         const uint32_t c = nit * WAVE + lane;
         if (c < nchunks) {
             float fq[VEC], fp[VEC];
@@ -96,7 +101,16 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
             account(fq, fp);
         }
     }
-    const double Z = wave_sum((double)hi + (double)s + (double)s1);
+    double Z = wave_sum((double)hi + (double)s + (double)s1);
+    if constexpr (W > 1) {
+        __shared__ double part[W];
+        if (lane == 0) part[wv] = Z;
+        __syncthreads();
+        if (wv > 0) return;
+        Z = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) Z += part[w];
+    }
     if (lane == 0) A.zexact[t] = (float)Z;
 }
 
@@ -105,16 +119,18 @@ __global__ __launch_bounds__(64) void zexact_kernel(ZExactArgs A)
 // off a third tensor.  One wavefront per row, one sweep: per-lane exponent reference (moved only
 // when a chunk maximum exceeds it by the margin) and sum, combined across the wave at the end.
 // =================================================================================================
-template <class ET>
-__global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
+// W > 1: rows split over W wavefronts as in zexact_kernel.
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W) void token_logprob_kernel(LogprobArgs A)
 {
     constexpr int VEC = ET::VEC;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
     const int64_t t = blockIdx.x;
     const int x = A.ids[t];
     const int64_t V = A.V;
     if (x < 0 || x >= V) {
-        if (lane == 0) A.out[t] = x < 0 ? 0.f : __uint_as_float(0x7fc00000u);
+        if (threadIdx.x == 0) A.out[t] = x < 0 ? 0.f : __uint_as_float(0x7fc00000u);
         return;
     }
     const char *row = (const char *)A.logits + (size_t)t * (size_t)A.stride * ET::ESZ;
@@ -141,13 +157,15 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
             if (--until_fold == 0) { hi += s; s = 0.f; until_fold = BLOCK_CHUNKS; }
         }
     };
-    if (nit > 0) {
+    const uint32_t it_lo = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)wv / W) : 0u;
+    const uint32_t it_hi = W > 1 ? (uint32_t)((uint64_t)nit * (uint32_t)(wv + 1) / W) : nit;
+    if (it_hi > it_lo) {
         constexpr int D = 4;
-        const uint32_t last = nit - 1;
+        const uint32_t last = it_hi - 1;
         u32x4 w[D];
 #pragma unroll
-        for (int d = 0; d < D; ++d) w[d] = stream_load(v + (((uint32_t)d < last ? (uint32_t)d : last) * WAVE + lane));
-        for (uint32_t it = 0; it < nit; it += D) {
+        for (int d = 0; d < D; ++d) w[d] = stream_load(v + ((it_lo + (uint32_t)d < last ? it_lo + (uint32_t)d : last) * WAVE + lane));
+        for (uint32_t it = it_lo; it < it_hi; it += D) {
             u32x4 c[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) c[d] = w[d];
@@ -155,7 +173,7 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
             for (int d = 0; d < D; ++d) w[d] = stream_load(v + ((it + D + d < last ? it + D + d : last) * WAVE + lane));
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                if (d == 0 || it + d < nit) {
+                if (d == 0 || it + d < it_hi) {
                     float f[VEC];
                     ET::unpack(c[d], f);
                     consume(f, true);
@@ -163,7 +181,7 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
             }
         }
     }
-    {
+    if (W == 1 || wv == W - 1) {                            // the remainder belongs to the last wave
         const uint32_t c = nit * WAVE + lane;
         if (c < nchunks) {
             float f[VEC];
@@ -172,8 +190,22 @@ __global__ __launch_bounds__(64) void token_logprob_kernel(LogprobArgs A)
         }
     }
     // combine the 64 (reference, sum) pairs: common reference = the largest, sums rescaled to it
-    const float Mw = uniform_f(wave_max(M2));
-    const double S = wave_sum(M2 == M2_UNSET ? 0.0 : ((double)hi + (double)s) * (double)__builtin_amdgcn_exp2f(M2 - Mw));
+    float Mw = uniform_f(wave_max(M2));
+    double S = wave_sum(M2 == M2_UNSET ? 0.0 : ((double)hi + (double)s) * (double)__builtin_amdgcn_exp2f(M2 - Mw));
+    if constexpr (W > 1) {                                  // the same combination once more, over the waves
+        __shared__ double part_s[W];
+        __shared__ float part_m[W];
+        if (lane == 0) { part_s[wv] = S; part_m[wv] = Mw; }
+        __syncthreads();
+        if (wv > 0) return;
+        float Mall = part_m[0];
+#pragma unroll
+        for (int w = 1; w < W; ++w) Mall = fmaxf(Mall, part_m[w]);
+        S = 0.0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) S += part_s[w] * (double)__builtin_amdgcn_exp2f(part_m[w] - Mall);
+        Mw = Mall;
+    }
     const double lse = ((double)Mw + log2_of_sum(S)) * LN2_D;
     const double lp = (double)ET::load1(row, x) - lse;
     if (lane == 0) A.out[t] = isfinite(lse) ? (float)lp : __uint_as_float(0x7fc00000u);
@@ -952,10 +984,23 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
 
 // ---- launchers ------------------------------------------------------------------------------
 
+// Small batches of long rows: four waves per row in the plain sweeps (the same rule as the row stage:
+// T <= 1792 and at least two sweep iterations per wave).
+static bool split_rows(int64_t T, int64_t V, int dtype)
+{
+    const int64_t iterations = V / (dtype == JP_BF16 ? 8 : 4) / WAVE;
+    return T <= 1792 && iterations >= 8;
+}
+
 hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
     const dim3 grid((unsigned)a.T), block(WAVE);
+    if (split_rows(a.T, a.V, dtype)) {
+        if (dtype == JP_BF16) hipLaunchKernelGGL((zexact_kernel<Bf16Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        else hipLaunchKernelGGL((zexact_kernel<F32Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        return hipGetLastError();
+    }
     if (dtype == JP_BF16) hipLaunchKernelGGL((zexact_kernel<Bf16Elem>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((zexact_kernel<F32Elem>), grid, block, 0, st, a);
     return hipGetLastError();
@@ -973,6 +1018,11 @@ hipError_t launch_token_logprob(const LogprobArgs &a, int dtype, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
     const dim3 grid((unsigned)a.T), block(WAVE);
+    if (split_rows(a.T, a.V, dtype)) {
+        if (dtype == JP_BF16) hipLaunchKernelGGL((token_logprob_kernel<Bf16Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        else hipLaunchKernelGGL((token_logprob_kernel<F32Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        return hipGetLastError();
+    }
     if (dtype == JP_BF16) hipLaunchKernelGGL((token_logprob_kernel<Bf16Elem>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((token_logprob_kernel<F32Elem>), grid, block, 0, st, a);
     return hipGetLastError();
