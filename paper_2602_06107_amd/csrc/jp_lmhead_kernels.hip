@@ -3,7 +3,8 @@
 // projection, and handed to the row kernel chunk by chunk, so the [T, V] logit tensors never
 // exist.  Two kernels live here:
 //   * transpose_chunk_kernel: W[d, V] (vocabulary contiguous) -> Wt[n, d] for the columns of one
-//     chunk, so that both GEMM operands are contiguous along the contraction dimension;
+//     chunk, so that both GEMM operands are contiguous along the contraction dimension (16-byte
+//     pieces on both sides, through an LDS tile);
 //   * gemm_tn_kernel: C[M, N] = A[M, K] * Bt[N, K]^T with 256x256x64 workgroup tiles, XOR-swizzled
 //     LDS tiles filled straight from global memory round a five-slot ring, 2x2 waves of 128x128
 //     (4x4 MFMA blocks each).
@@ -47,26 +48,51 @@ __device__ __forceinline__ int tile_offset(int row, int piece) { return row * RO
 
 // -------------------------------------------------------------------------------------------------
 // Wt[n, kk] = W[kk, v0 + n] for n < ncols (zero for ncols <= n < npad), kk < d.
+// A workgroup moves a tile of 64 k-rows x 128 vocabulary columns: it reads 16-byte pieces along
+// the vocabulary (the contiguous direction of W), scatters their eight elements into an LDS tile
+// held column-major, and writes 16-byte pieces along k (the contiguous direction of Wt).  Pieces
+// that are not 16-byte aligned in W (v0 or ldw not a multiple of 8), or that cross the end of
+// the chunk, are read element by element.  d is a multiple of 64 (checked by the caller).
 // -------------------------------------------------------------------------------------------------
+constexpr int TR_K = 64, TR_N = 128, TR_PITCH = TR_K + 2;     // LDS pitch in elements: an odd number of 32-bit words,
+                                                              // so the eight rows a piece scatters to fall into different banks
 __global__ __launch_bounds__(256) void transpose_chunk_kernel(const uint16_t *__restrict__ W, int64_t ldw,
                                                               int d, int64_t v0, int ncols, int npad,
                                                               uint16_t *__restrict__ Wt)
 {
-    __shared__ uint16_t tile[64][66];
-    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    __shared__ __attribute__((aligned(4))) uint16_t tile[TR_N][TR_PITCH];
+    const int n0 = blockIdx.x * TR_N, k0 = blockIdx.y * TR_K;
+    const int tid = threadIdx.x;
+    const bool aligned = ((v0 | ldw) & 7) == 0 && ((uintptr_t)W & 15) == 0;
+    {
+        const int piece = tid & 15, krow = tid >> 4;          // 16 pieces of 8 columns per k-row, 16 k-rows per pass
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int kk = i * 4 + ty, n = n0 + tx;
-        uint16_t v = 0;
-        if (k0 + kk < d && n < ncols) v = W[(int64_t)(k0 + kk) * ldw + v0 + n];
-        tile[kk][tx] = v;
+        for (int pass = 0; pass < TR_K / 16; ++pass) {
+            const int kk = pass * 16 + krow, n = n0 + piece * 8;
+            uint16_t e[8];
+            const uint16_t *src = W + (int64_t)(k0 + kk) * ldw + v0 + n;
+            if (aligned && n + 8 <= ncols) {
+                const u32x4 v = *(const u32x4 *)src;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { e[2 * j] = (uint16_t)(v[j] & 0xffffu); e[2 * j + 1] = (uint16_t)(v[j] >> 16); }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) e[j] = n + j < ncols ? src[j] : (uint16_t)0;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) tile[piece * 8 + j][kk] = e[j];
+        }
     }
     __syncthreads();
+    {
+        const int piece = tid & 7, nrow = tid >> 3;           // 8 pieces of 8 k per column, 32 columns per pass
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int n = n0 + i * 4 + ty, kk = k0 + tx;
-        if (n < npad && kk < d) Wt[(int64_t)n * d + kk] = tile[tx][i * 4 + ty];
+        for (int pass = 0; pass < TR_N / 32; ++pass) {
+            const int nl = pass * 32 + nrow, n = n0 + nl;
+            const uint32_t *row = (const uint32_t *)&tile[nl][piece * 8];      // (4-byte aligned: the pitch is 33 words)
+            const u32x4 v = {row[0], row[1], row[2], row[3]};
+            if (n < npad) *(u32x4 *)(Wt + (int64_t)n * d + k0 + piece * 8) = v;
+        }
     }
 }
 
@@ -281,7 +307,7 @@ hipError_t launch_copy_rows_chunk(const void *W, int d, int64_t v0, int ncols, i
 hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0, int ncols, int npad,
                                   void *Wt, hipStream_t st)
 {
-    const dim3 grid((unsigned)((npad + 63) / 64), (unsigned)((d + 63) / 64));
+    const dim3 grid((unsigned)((npad + TR_N - 1) / TR_N), (unsigned)(d / TR_K));
     hipLaunchKernelGGL(transpose_chunk_kernel, grid, dim3(256), 0, st, (const uint16_t *)W, ldw, d, v0, ncols,
                        npad, (uint16_t *)Wt);
     return hipGetLastError();
