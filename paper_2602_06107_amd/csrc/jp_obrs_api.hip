@@ -318,6 +318,7 @@ jp_status jp_obrs_forward_lmhead_stored(const void *H_policy, int64_t d_policy, 
                 g.Bt[0] = base + pl.off_wt_p;
             } else if (ncols == nthis) {
                 g.Bt[0] = (const char *)W_policy + (size_t)v0 * (size_t)d_policy * 2;
+                if (jp::launch_touch_rows(g.Bt[0], (int64_t)nthis * d_policy * 2, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
             } else {
                 if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
                 g.Bt[0] = base + pl.off_wt_p;
@@ -408,6 +409,8 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
                 // [V, d] weights: a chunk of whole column tiles is already the GEMM's second operand
                 g.Bt[0] = (const char *)W_policy + (size_t)v0 * (size_t)d_policy * 2;
                 g.Bt[1] = (const char *)W_actor + (size_t)v0 * (size_t)d_actor * 2;
+                if (jp::launch_touch_rows(g.Bt[0], (int64_t)nthis * d_policy * 2, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
+                if (jp::launch_touch_rows(g.Bt[1], (int64_t)nthis * d_actor * 2, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;
             } else {
                 if (jp::launch_copy_rows_chunk(W_policy, (int)d_policy, v0, ncols, nthis, base + pl.off_wt_p, st) != hipSuccess) return JP_ERR_HIP;
                 if (jp::launch_copy_rows_chunk(W_actor, (int)d_actor, v0, ncols, nthis, base + pl.off_wt_a, st) != hipSuccess) return JP_ERR_HIP;

@@ -140,6 +140,7 @@ constexpr int LMHEAD_N_ALIGN = 256;   // GEMM column tile
 hipError_t launch_transpose_chunk(const void *W, int64_t ldw, int d, int64_t v0, int ncols, int npad,
                                   void *Wt, hipStream_t st);
 hipError_t launch_copy_rows_chunk(const void *W, int d, int64_t v0, int ncols, int npad, void *Wt, hipStream_t st);
+hipError_t launch_touch_rows(const void *W, int64_t bytes, void *sink, hipStream_t st);   // read and drop: warms the caches
 hipError_t launch_gemm_pair(const GemmArgs &g, hipStream_t st);
 hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st);   // fp32 logits chunk, carried state
 hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st);
