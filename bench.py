@@ -21,8 +21,10 @@ sys.path.insert(0, ROOT)
 METRIC = "OBRS tokens/sec at V=151936 bf16 on 1 MI355X; achieved HBM GB/s vs peak"
 HBM_PEAK_GBS = 8000.0
 
-KERNEL_SOURCES = ("paper_2602_06107_amd/csrc/jp_row_kernel.hip", "paper_2602_06107_amd/csrc/jp_device_utils.h",
-                  "paper_2602_06107_amd/csrc/jp_obrs_internal.h")
+KERNEL_SOURCES = ("paper_2602_06107_amd/csrc/jp_row_kernel.hip", "paper_2602_06107_amd/csrc/jp_device_utils.h")
+# of the header shared by all kernels only the row kernel's own part counts: its argument struct and
+# the row record (from "struct RowArgs" up to "struct ZExactArgs")
+KERNEL_ARGS_HEADER = ("paper_2602_06107_amd/csrc/jp_obrs_internal.h", b"struct RowArgs", b"struct ZExactArgs")
 
 
 def kernel_source_digest() -> str:
@@ -32,6 +34,10 @@ def kernel_source_digest() -> str:
     for rel in KERNEL_SOURCES:
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
+    rel, first, last = KERNEL_ARGS_HEADER
+    with open(os.path.join(ROOT, rel), "rb") as f:
+        text = f.read()
+    h.update(text[text.index(first):text.index(last)])
     return h.hexdigest()[:16]
 
 
