@@ -134,17 +134,7 @@ jp_status rows_impl(const void *actor, const void *policy, int64_t T, int64_t V,
     const bool lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) != 0;
     a.topk_a_lq = lp ? out->topk_actor_logq : nullptr;
     a.topk_p_lp = lp ? out->topk_policy_logp : nullptr;
-    // Small batches: one wave per row leaves most of the chip idle, and a single wave needs ~0.14 ms
-    // for a row of 152 k logits whatever else runs.  Up to T = 1792 a row is split over four waves
-    // (two at k > 128), provided every wave still gets at least two sweep iterations; measured on
-    // V = 151936, k = 64: 2.1x at T = 256, 1.7x at 512, 1.15x at 1024, 1.1x at 1536, and a loss
-    // from T = 2048 on, where one wave per row already fills the chip.
-    a.waves = 1;
-    if (!(prm->flags & JP_FLAG_ONE_WAVE_PER_ROW)) {
-        const int64_t iterations = V / (int64_t)(16 / esz) / 64;
-        if (T <= 1792 && iterations >= 8) a.waves = 4;
-        else if (T <= 1792 && iterations >= 4) a.waves = 2;
-    }
+    a.waves = (prm->flags & JP_FLAG_ONE_WAVE_PER_ROW) ? 1 : jp::waves_per_row(T, V, (int)esz);
     if (jp::launch_rows(a, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
 
     if (prm->flags & JP_FLAG_EXACT_Z) {

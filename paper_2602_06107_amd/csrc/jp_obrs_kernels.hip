@@ -984,13 +984,8 @@ __global__ __launch_bounds__(FINALIZE_THREADS) void finalize_kernel(FinalizeArgs
 
 // ---- launchers ------------------------------------------------------------------------------
 
-// Small batches of long rows: four waves per row in the plain sweeps (the same rule as the row stage:
-// T <= 1792 and at least two sweep iterations per wave).
-static bool split_rows(int64_t T, int64_t V, int dtype)
-{
-    const int64_t iterations = V / (dtype == JP_BF16 ? 8 : 4) / WAVE;
-    return T <= 1792 && iterations >= 8;
-}
+// Small batches of long rows: four waves per row in the plain sweeps, by the rule of the row stage.
+static bool split_rows(int64_t T, int64_t V, int dtype) { return waves_per_row(T, V, dtype == JP_BF16 ? 2 : 4) == 4; }
 
 hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)
 {
