@@ -79,8 +79,9 @@ enum {
     JP_FLAG_ONE_WAVE_PER_ROW = 32 /* never split a row over several wavefronts (the library does
                                    so by itself for small batches, T <= 1792, in the two-tensor
                                    form; the index lists are the same either way, floats agree
-                                   to rounding of the log-sum-exp; the exact-normaliser and
-                                   token-log-probability sweeps always split by that rule)   */
+                                   to rounding of the log-sum-exp; the exact-normaliser sweep
+                                   follows the row stage, jp_obrs_token_logprob, which takes
+                                   no flags, always splits by that rule)                     */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */

@@ -142,6 +142,7 @@ jp_status rows_impl(const void *actor, const void *policy, int64_t T, int64_t V,
         z.actor = actor; z.policy = policy; z.T = T; z.V = V; z.stride = row_stride;
         z.lse_q = w.lse_q; z.lse_p = w.lse_p; z.rowflag = w.rowflag; z.lambda = prm->lambda;
         z.zexact = out->z_exact ? out->z_exact : w.zexact;
+        z.waves = a.waves;
         if (jp::launch_zexact(z, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
     }
     return JP_OK;

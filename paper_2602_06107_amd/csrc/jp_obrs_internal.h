@@ -64,6 +64,7 @@ struct ZExactArgs {
     const uint8_t *rowflag;
     float lambda;
     float *zexact;
+    int waves;                        // wavefronts per row: 4 or 1 (as the row stage chose)
 };
 
 struct FinalizeArgs {

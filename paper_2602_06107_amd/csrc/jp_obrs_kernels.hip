@@ -991,7 +991,7 @@ hipError_t launch_zexact(const ZExactArgs &a, int dtype, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
     const dim3 grid((unsigned)a.T), block(WAVE);
-    if (split_rows(a.T, a.V, dtype)) {
+    if (a.waves >= 4) {
         if (dtype == JP_BF16) hipLaunchKernelGGL((zexact_kernel<Bf16Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
         else hipLaunchKernelGGL((zexact_kernel<F32Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
         return hipGetLastError();
