@@ -80,8 +80,9 @@ enum {
                                    so by itself for small batches, T <= 1792, in the two-tensor
                                    form; the index lists are the same either way, floats agree
                                    to rounding of the log-sum-exp; the exact-normaliser sweep
-                                   follows the row stage, jp_obrs_token_logprob, which takes
-                                   no flags, always splits by that rule)                     */
+                                   follows the row stage; jp_obrs_token_logprob and
+                                   jp_obrs_lambda_for_budget, which take no flags, always
+                                   split by that rule)                                       */
 };
 
 enum {                          /* bits of jp_obrs_stats.error_flags */

@@ -247,26 +247,31 @@ constexpr double BUDGET_FIX31 = 2147483648.0;              // 2^31
 
 // Sweep of one row pair with `account(fq, fp)` called on every chunk (padding of the ragged last
 // chunk arrives as -inf in both rows: probability 0 under both models).
+// part / parts: the wave takes the part-th of `parts` contiguous runs of the sweep iterations (rows
+// split over the waves of a workgroup); the remainder belongs to the last part.
 template <class ET, class F>
-__device__ __forceinline__ void budget_for_each_chunk(const char *rowq, const char *rowp, int64_t V, F account)
+__device__ __forceinline__ void budget_for_each_chunk(const char *rowq, const char *rowp, int64_t V, F account,
+                                                      int part = 0, int parts = 1)
 {
     constexpr int VEC = ET::VEC;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
     const uint32_t nfull = (uint32_t)(V / VEC);
     const int tail = (int)(V - (int64_t)nfull * VEC);
     const uint32_t nchunks = nfull + (tail ? 1u : 0u);
-    const uint32_t nit = nfull / WAVE;                  // iterations in which every lane has a full chunk
-    if (nit > 0) {
+    const uint32_t nit_all = nfull / WAVE;              // iterations in which every lane has a full chunk
+    const uint32_t it_lo = (uint32_t)((uint64_t)nit_all * (uint32_t)part / (uint32_t)parts);
+    const uint32_t nit = (uint32_t)((uint64_t)nit_all * (uint32_t)(part + 1) / (uint32_t)parts);   // end of this run
+    if (nit > it_lo) {
         constexpr int D = 3;                            // loads in flight per tensor and lane
         const uint32_t last = nit - 1;
         u32x4 wq[D], wp[D];
 #pragma unroll
         for (int d2 = 0; d2 < D; ++d2) {
-            const uint32_t n = ((uint32_t)d2 < last ? (uint32_t)d2 : last) * WAVE + lane;
+            const uint32_t n = (it_lo + (uint32_t)d2 < last ? it_lo + (uint32_t)d2 : last) * WAVE + lane;
             wq[d2] = stream_load(as_global_vec(rowq) + n);
             wp[d2] = stream_load(as_global_vec(rowp) + n);
         }
-        for (uint32_t it = 0; it < nit; it += D) {
+        for (uint32_t it = it_lo; it < nit; it += D) {
 #pragma unroll
             for (int d2 = 0; d2 < D; ++d2) {
                 const u32x4 cq = wq[d2], cp = wp[d2];
@@ -282,8 +287,8 @@ __device__ __forceinline__ void budget_for_each_chunk(const char *rowq, const ch
             }
         }
     }
-    const uint32_t c = nit * WAVE + lane;
-    if (c < nchunks) {
+    const uint32_t c = nit_all * WAVE + lane;
+    if (part == parts - 1 && c < nchunks) {
         float fq[VEC], fp[VEC];
         load_chunk<ET>(rowq, c, nfull, tail, fq);
         load_chunk<ET>(rowp, c, nfull, tail, fp);
@@ -297,12 +302,13 @@ __device__ __forceinline__ void budget_for_each_chunk(const char *rowq, const ch
 // goes to entry 0, which nobody reads.
 template <class ET>
 __device__ __forceinline__ void budget_coarse_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
-                                                    uint32_t *hist)
+                                                    uint32_t *hist, int part = 0, int parts = 1)
 {
     constexpr int VEC = ET::VEC;
-    const int lane = threadIdx.x;
-    for (int e = lane; e < 2 * (BUDGET_COARSE + 1); e += WAVE) hist[e] = 0u;
-    lds_sync();
+    const int lane = threadIdx.x & (WAVE - 1);
+    // (rows split over `parts` waves: they share the bins, whose integer sums do not depend on order)
+    for (int e = threadIdx.x; e < 2 * (BUDGET_COARSE + 1); e += WAVE * parts) hist[e] = 0u;
+    if (parts > 1) __syncthreads(); else lds_sync();
     const float dA = Ap - Aq;
     const float inv_w = 1.f / BUDGET_COARSE_W;
     const float off = BUDGET_CRANGE * inv_w + 1.f;
@@ -316,14 +322,15 @@ __device__ __forceinline__ void budget_coarse_sweep(const char *rowq, const char
             b = b < 1 ? (d >= -BUDGET_RANGE ? 1 : 0) : (b < BUDGET_COARSE ? b : BUDGET_COARSE);
             atomicAdd(&hist[((uint32_t)b << 1) | copy], (uint32_t)__builtin_fmaf(q, (float)BUDGET_FIX31, 0.5f));
         }
-    });
-    lds_sync();
+    }, part, parts);
+    if (parts > 1) __syncthreads(); else lds_sync();
 }
 
 // The smallest finite log2 ratio of a row pair (one more sweep, only for a budget at the keepable
 // mass, where every lambda up to the smallest ratio accepts everything).
 template <class ET>
-__device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap)
+__device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
+                                                  int part = 0, int parts = 1)
 {
     constexpr int VEC = ET::VEC;
     const float dA = Ap - Aq;
@@ -334,7 +341,7 @@ __device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *
             const float d = __builtin_fmaf(fp[j] - fq[j], LOG2E_F, -dA);
             dmin = (d > -3.0e38f && d < 3.0e38f) ? fminf(dmin, d) : dmin;
         }
-    });
+    }, part, parts);
     return -uniform_f(wave_max(-dmin));
 }
 
@@ -344,10 +351,12 @@ __device__ __forceinline__ float budget_min_ratio(const char *rowq, const char *
 // into the last bin).
 template <class ET>
 __device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *rowp, int64_t V, float Aq, float Ap,
-                                                  float lo, float hi, double *hq, double *hp, double &qa, double &pb)
+                                                  float lo, float hi, double *hq, double *hp, double &qa, double &pb,
+                                                  int part = 0, int parts = 1)
 {
+    // (rows split over waves: every wave has bins of its own, hq / hp, and returns its share of qa, pb)
     constexpr int VEC = ET::VEC;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
     for (int e = lane; e < BUDGET_FINE + 1; e += WAVE) { hq[e] = 0.0; hp[e] = 0.0; }
     lds_sync();
     const float width = hi - lo;
@@ -387,7 +396,7 @@ __device__ __forceinline__ void budget_fine_sweep(const char *rowq, const char *
                 }
             }
         }
-    });
+    }, part, parts);
     lds_sync();
     if (lane == 0) { hq[BUDGET_FINE - 1] += hq[BUDGET_FINE]; hp[BUDGET_FINE - 1] += hp[BUDGET_FINE]; }
     lds_sync();
@@ -545,20 +554,30 @@ __device__ __forceinline__ int budget_after_fine(const BudgetFound &f, double ep
     return BUDGET_SEARCH;
 }
 
-template <class ET>
-__global__ __launch_bounds__(64, 6) void budget_kernel(BudgetArgs A)
+// W > 1: a row goes to W wavefronts of one workgroup (small batches, as in the row stage).  Every
+// wave sweeps its run of the row; the integer bins of the first sweep are shared, the float64 bins
+// of the exact sweeps are per wave and added up in wave order, and wave 0 alone runs the scans and
+// tells the others through LDS how the search goes on.
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W, W == 1 ? 6 : 4) void budget_kernel(BudgetArgs A)
 {
-    // coarse bins (2 x 513 32-bit words); later the fine q / p bins (2 x 257 doubles)
+    // coarse bins (2 x 513 32-bit words); for W = 1 later the fine q / p bins (2 x 257 doubles)
     __shared__ __attribute__((aligned(8))) uint32_t hist[4 * (BUDGET_FINE + 1) > 2 * (BUDGET_COARSE + 1) ? 4 * (BUDGET_FINE + 1) : 2 * (BUDGET_COARSE + 1)];
     __shared__ double sq_[WAVE], sp_[WAVE];
-    double *const hq = (double *)hist, *const hp = hq + BUDGET_FINE + 1;
-    const int lane = threadIdx.x;
+    __shared__ double fine[W > 1 ? W : 1][W > 1 ? 2 * (BUDGET_FINE + 1) : 1];   // split rows: the fine bins of every wave
+    __shared__ double s_out[W > 1 ? W : 1][2];                                  // ... and its mass outside the bracket
+    __shared__ float s_min[W > 1 ? W : 1];
+    __shared__ float s_lo, s_hi;
+    __shared__ int s_state;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
+    double *const hq = W > 1 ? fine[wv] : (double *)hist, *const hp = hq + BUDGET_FINE + 1;
     const int64_t t = blockIdx.x;
     const float NaN = __uint_as_float(0x7fc00000u);
     const uint8_t flag = A.rowflag[t];
     const float abar_f = A.row_target ? A.row_target[t] : A.target;
     if (flag != ROW_OK || !(abar_f > 0.f) || abar_f > 1.f) {
-        if (lane == 0) A.lambda_out[t] = flag == ROW_PADDING ? 0.f : NaN;
+        if (threadIdx.x == 0) A.lambda_out[t] = flag == ROW_PADDING ? 0.f : NaN;
         return;
     }
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
@@ -568,28 +587,65 @@ __global__ __launch_bounds__(64, 6) void budget_kernel(BudgetArgs A)
     const double goal = (double)abar_f;
     const double eps = goal * (double)A.eps_rel;
 
-    budget_coarse_sweep<ET>(rowq, rowp, A.V, Aq, Ap, hist);
-    double cq[BUDGET_CPL];
-#pragma unroll
-    for (int j = 0; j < BUDGET_CPL; ++j) {
-        const int b = 1 + lane * BUDGET_CPL + j;                  // (entry 0 holds what no lambda keeps)
-        cq[j] = ((double)hist[2 * b] + (double)hist[2 * b + 1]) / BUDGET_FIX31;
-    }
+    budget_coarse_sweep<ET>(rowq, rowp, A.V, Aq, Ap, hist, wv, W);
     float lo = -BUDGET_RANGE, hi = BUDGET_RANGE;
     double lambda = 0.0;
-    int state = budget_after_coarse(goal, cq, sq_, sp_, lo, hi);
+    int state = BUDGET_SEARCH;
+    if (wv == 0) {
+        double cq[BUDGET_CPL];
+#pragma unroll
+        for (int j = 0; j < BUDGET_CPL; ++j) {
+            const int b = 1 + lane * BUDGET_CPL + j;              // (entry 0 holds what no lambda keeps)
+            cq[j] = ((double)hist[2 * b] + (double)hist[2 * b + 1]) / BUDGET_FIX31;
+        }
+        state = budget_after_coarse(goal, cq, sq_, sp_, lo, hi);
+        if (W > 1 && lane == 0) { s_state = state; s_lo = lo; s_hi = hi; }
+    }
+    if constexpr (W > 1) {
+        __syncthreads();
+        state = s_state; lo = s_lo; hi = s_hi;
+    }
     for (int sweep = 1; sweep < BUDGET_MAX_SWEEPS && state == BUDGET_SEARCH; ++sweep) {
         double qa, pb;
-        budget_fine_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb);
-        const double A_above = qa, B_below = wave_sum(pb);
-        double fq[BUDGET_FPL], fp[BUDGET_FPL];
+        budget_fine_sweep<ET>(rowq, rowp, A.V, Aq, Ap, lo, hi, hq, hp, qa, pb, wv, W);
+        double A_above = qa, B_below = wave_sum(pb);
+        if constexpr (W > 1) {
+            if (lane == 0) { s_out[wv][0] = A_above; s_out[wv][1] = B_below; }
+            __syncthreads();                                  // every wave's bins and outside masses are complete
+        }
+        if (wv == 0) {
+            double fq[BUDGET_FPL], fp[BUDGET_FPL];
 #pragma unroll
-        for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] = hq[lane * BUDGET_FPL + j]; fp[j] = hp[lane * BUDGET_FPL + j]; }
-        const BudgetFound f = budget_scan<BUDGET_FPL>(goal, A_above, B_below, fq, fp, lo, (hi - lo) / (float)BUDGET_FINE, sq_, sp_);
-        state = budget_after_fine(f, eps, sweep == BUDGET_MAX_SWEEPS - 1, lo, hi, lambda);
+            for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] = hq[lane * BUDGET_FPL + j]; fp[j] = hp[lane * BUDGET_FPL + j]; }
+            if constexpr (W > 1) {
+#pragma unroll
+                for (int w = 1; w < W; ++w) {                 // in wave order: the same sums on every run
+                    const double *oq = fine[w], *op = oq + BUDGET_FINE + 1;
+#pragma unroll
+                    for (int j = 0; j < BUDGET_FPL; ++j) { fq[j] += oq[lane * BUDGET_FPL + j]; fp[j] += op[lane * BUDGET_FPL + j]; }
+                    A_above += s_out[w][0]; B_below += s_out[w][1];
+                }
+            }
+            const BudgetFound f = budget_scan<BUDGET_FPL>(goal, A_above, B_below, fq, fp, lo, (hi - lo) / (float)BUDGET_FINE, sq_, sp_);
+            state = budget_after_fine(f, eps, sweep == BUDGET_MAX_SWEEPS - 1, lo, hi, lambda);
+            if (W > 1 && lane == 0) { s_state = state; s_lo = lo; s_hi = hi; }
+        }
+        if constexpr (W > 1) {
+            __syncthreads();                                  // (also: nobody reads the bins any more)
+            state = s_state; lo = s_lo; hi = s_hi;
+        }
     }
-    if (state == BUDGET_KEEP_ALL) lambda = (double)__builtin_amdgcn_exp2f(budget_min_ratio<ET>(rowq, rowp, A.V, Aq, Ap));
-    if (lane == 0) A.lambda_out[t] = (float)lambda;
+    if (state == BUDGET_KEEP_ALL) {
+        float dmin = budget_min_ratio<ET>(rowq, rowp, A.V, Aq, Ap, wv, W);
+        if constexpr (W > 1) {
+            if (lane == 0) s_min[wv] = dmin;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < W; ++w) dmin = fminf(dmin, s_min[w]);
+        }
+        lambda = (double)__builtin_amdgcn_exp2f(dmin);
+    }
+    if (threadIdx.x == 0) A.lambda_out[t] = (float)lambda;
 }
 
 // The same search for one lambda of a whole batch, mean_t Z_t(lambda) = abar: the bins of all rows are
@@ -1027,6 +1083,11 @@ hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
     const dim3 grid((unsigned)a.T), block(WAVE);
+    if (split_rows(a.T, a.V, dtype)) {
+        if (dtype == JP_BF16) hipLaunchKernelGGL((budget_kernel<Bf16Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        else hipLaunchKernelGGL((budget_kernel<F32Elem, 4>), grid, dim3(4 * WAVE), 0, st, a);
+        return hipGetLastError();
+    }
     if (dtype == JP_BF16) hipLaunchKernelGGL((budget_kernel<Bf16Elem>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((budget_kernel<F32Elem>), grid, block, 0, st, a);
     return hipGetLastError();
