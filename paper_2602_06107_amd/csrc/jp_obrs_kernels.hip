@@ -669,21 +669,23 @@ __device__ __forceinline__ int float_order_int(float f)
     return i ^ ((i >> 31) & 0x7fffffff);
 }
 
-template <class ET>
-__global__ __launch_bounds__(64, 6) void budget_batch_coarse_kernel(BudgetArgs A, BudgetBatchState *S)
+// (W > 1 in the three sweep kernels below: rows split over W waves as in budget_kernel; the sums in
+// device memory are integers, so every wave adds its own share and nothing has to be merged.)
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W, W == 1 ? 6 : 4) void budget_batch_coarse_kernel(BudgetArgs A, BudgetBatchState *S)
 {
     __shared__ uint32_t hist[2 * (BUDGET_COARSE + 1)];
-    const int lane = threadIdx.x;
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
     const int64_t t = blockIdx.x;
     if (A.rowflag[t] != ROW_OK) return;
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
-    budget_coarse_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), hist);
-    for (int b = lane; b < BUDGET_COARSE; b += WAVE) {
+    budget_coarse_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), hist, wv, W);
+    for (int b = threadIdx.x; b < BUDGET_COARSE; b += WAVE * W) {
         const unsigned long long u = (unsigned long long)hist[2 * (b + 1)] + (unsigned long long)hist[2 * (b + 1) + 1];
         if (u) atomicAdd(&S->coarse[b], u);                   // 2^-31 units: integer sums, any order
     }
-    if (lane == 0) atomicAdd(&S->n_rows, 1ull);
+    if (threadIdx.x == 0) atomicAdd(&S->n_rows, 1ull);
 }
 
 __global__ __launch_bounds__(64) void budget_batch_after_coarse_kernel(BudgetBatchState *S, float target, float *out_lambda)
@@ -708,15 +710,16 @@ __global__ __launch_bounds__(64) void budget_batch_after_coarse_kernel(BudgetBat
 }
 
 // Only when the search ended with "every lambda up to the smallest ratio": that ratio, over all rows.
-template <class ET>
-__global__ __launch_bounds__(64, 6) void budget_batch_min_ratio_kernel(BudgetArgs A, BudgetBatchState *S)
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W, W == 1 ? 6 : 4) void budget_batch_min_ratio_kernel(BudgetArgs A, BudgetBatchState *S)
 {
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
     const int64_t t = blockIdx.x;
     if (S->done != BUDGET_KEEP_ALL || A.rowflag[t] != ROW_OK) return;
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
-    const float dmin = budget_min_ratio<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D));
-    if (threadIdx.x == 0) atomicMin(&S->dmin_ord, float_order_int(dmin));
+    const float dmin = budget_min_ratio<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), wv, W);
+    if ((threadIdx.x & (WAVE - 1)) == 0) atomicMin(&S->dmin_ord, float_order_int(dmin));
 }
 
 __global__ void budget_batch_min_ratio_finish_kernel(BudgetBatchState *S, float *out_lambda)
@@ -729,17 +732,19 @@ __global__ void budget_batch_min_ratio_finish_kernel(BudgetBatchState *S, float 
     *out_lambda = (float)S->lambda;
 }
 
-template <class ET>
-__global__ __launch_bounds__(64, 6) void budget_batch_fine_kernel(BudgetArgs A, BudgetBatchState *S)
+template <class ET, int W = 1>
+__global__ __launch_bounds__(64 * W, W == 1 ? 6 : 4) void budget_batch_fine_kernel(BudgetArgs A, BudgetBatchState *S)
 {
-    __shared__ double hq[BUDGET_FINE + 1], hp[BUDGET_FINE + 1];
-    const int lane = threadIdx.x;
+    __shared__ double bins[W][2 * (BUDGET_FINE + 1)];        // every wave its own
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
+    double *const hq = bins[wv], *const hp = hq + BUDGET_FINE + 1;
     const int64_t t = blockIdx.x;
     if (S->done != BUDGET_SEARCH || A.rowflag[t] != ROW_OK) return;
     const char *rowq = (const char *)A.actor + (size_t)t * (size_t)A.stride * ET::ESZ;
     const char *rowp = (const char *)A.policy + (size_t)t * (size_t)A.stride * ET::ESZ;
     double qa, pb;
-    budget_fine_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), S->lo, S->hi, hq, hp, qa, pb);
+    budget_fine_sweep<ET>(rowq, rowp, A.V, (float)(A.lse_q[t] * LOG2E_D), (float)(A.lse_p[t] * LOG2E_D), S->lo, S->hi, hq, hp, qa, pb, wv, W);
     const double A_above = qa, B_below = wave_sum(pb);
     for (int b = lane; b < BUDGET_FINE; b += WAVE) {
         const unsigned long long uq = (unsigned long long)(hq[b] * 4294967296.0), up = (unsigned long long)(hp[b] * 4294967296.0);
@@ -1093,29 +1098,33 @@ hipError_t launch_budget(const BudgetArgs &a, int dtype, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState *S, float *out_lambda, hipStream_t st)
+template <class ET, int W>
+static void launch_budget_batch_w(const BudgetArgs &a, BudgetBatchState *S, float *out_lambda, hipStream_t st)
 {
-    const dim3 grid((unsigned)(a.T > 0 ? a.T : 1)), block(WAVE);
-    hipLaunchKernelGGL(budget_batch_init_kernel, dim3(1), block, 0, st, S);
-    if (a.T > 0) {
-        if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_coarse_kernel<Bf16Elem>), grid, block, 0, st, a, S);
-        else hipLaunchKernelGGL((budget_batch_coarse_kernel<F32Elem>), grid, block, 0, st, a, S);
-    }
-    hipLaunchKernelGGL(budget_batch_after_coarse_kernel, dim3(1), block, 0, st, S, a.target, out_lambda);
+    const dim3 grid((unsigned)(a.T > 0 ? a.T : 1)), one(WAVE), block(WAVE * W);
+    hipLaunchKernelGGL(budget_batch_init_kernel, dim3(1), one, 0, st, S);
+    if (a.T > 0) hipLaunchKernelGGL((budget_batch_coarse_kernel<ET, W>), grid, block, 0, st, a, S);
+    hipLaunchKernelGGL(budget_batch_after_coarse_kernel, dim3(1), one, 0, st, S, a.target, out_lambda);
     // the exact sweeps: as many launches as the search may need; once it has finished the rest return at once
     for (int sweep = 1; sweep < BUDGET_MAX_SWEEPS; ++sweep) {
-        if (a.T > 0) {
-            if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_fine_kernel<Bf16Elem>), grid, block, 0, st, a, S);
-            else hipLaunchKernelGGL((budget_batch_fine_kernel<F32Elem>), grid, block, 0, st, a, S);
-        }
-        hipLaunchKernelGGL(budget_batch_after_fine_kernel, dim3(1), block, 0, st, S, a.target, a.eps_rel,
+        if (a.T > 0) hipLaunchKernelGGL((budget_batch_fine_kernel<ET, W>), grid, block, 0, st, a, S);
+        hipLaunchKernelGGL(budget_batch_after_fine_kernel, dim3(1), one, 0, st, S, a.target, a.eps_rel,
                            sweep == BUDGET_MAX_SWEEPS - 1 ? 1 : 0, out_lambda);
     }
-    if (a.T > 0) {
-        if (dtype == JP_BF16) hipLaunchKernelGGL((budget_batch_min_ratio_kernel<Bf16Elem>), grid, block, 0, st, a, S);
-        else hipLaunchKernelGGL((budget_batch_min_ratio_kernel<F32Elem>), grid, block, 0, st, a, S);
+    if (a.T > 0) hipLaunchKernelGGL((budget_batch_min_ratio_kernel<ET, W>), grid, block, 0, st, a, S);
+    hipLaunchKernelGGL(budget_batch_min_ratio_finish_kernel, dim3(1), one, 0, st, S, out_lambda);
+}
+
+hipError_t launch_budget_batch(const BudgetArgs &a, int dtype, BudgetBatchState *S, float *out_lambda, hipStream_t st)
+{
+    const bool split = split_rows(a.T, a.V, dtype);
+    if (dtype == JP_BF16) {
+        if (split) launch_budget_batch_w<Bf16Elem, 4>(a, S, out_lambda, st);
+        else launch_budget_batch_w<Bf16Elem, 1>(a, S, out_lambda, st);
+    } else {
+        if (split) launch_budget_batch_w<F32Elem, 4>(a, S, out_lambda, st);
+        else launch_budget_batch_w<F32Elem, 1>(a, S, out_lambda, st);
     }
-    hipLaunchKernelGGL(budget_batch_min_ratio_finish_kernel, dim3(1), block, 0, st, S, out_lambda);
     return hipGetLastError();
 }
 
