@@ -527,6 +527,7 @@ jp_status jp_obrs_forward_stored(const void *policy_logits, int64_t T, int64_t V
         a.topk_p_lp = (prm->flags & JP_FLAG_TOPK_LOGPROBS) ? out->topk_policy_logp : nullptr;
         a.stored_ids = actor_topk_ids; a.stored_logq = actor_topk_logprob; a.stored_logq_x = actor_logprob_x;
         a.tail_rule = (int)tail_rule;
+        a.waves = (prm->flags & JP_FLAG_ONE_WAVE_PER_ROW) ? 1 : jp::waves_per_row(T, V, dt == JP_BF16 ? 2 : 4);
         if (jp::launch_rows_stored(a, (int)dt, st) != hipSuccess) return JP_ERR_HIP;
     }
     return finalize_impl(T, sampled_ids, uniforms, ref_logprob, prm, out, workspace, workspace_bytes, st,

@@ -197,7 +197,7 @@ __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, boo
 template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false, int W = 1>
 __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
-    static_assert(W == 1 || (!CARRY && !STORED), "rows are only split in the two-tensor form");
+    static_assert(W == 1 || !CARRY, "rows are not split in the vocabulary-chunked forms");
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
     constexpr int C = (KC >= 256 ? 3 : 4) * KC;   // descriptor buffer capacity per tensor
@@ -863,10 +863,26 @@ hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st)
     return launch_rows_k<F32Elem, Key64, true>(a, st);
 }
 
-template <class ET, class KT>
+template <class ET, class KT, bool SPLIT>
 static hipError_t launch_rows_stored_k(const RowArgs &a, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T), block(WAVE);
+    if constexpr (SPLIT) {
+        const int w = a.waves >= 4 && a.k <= 128 ? 4 : (a.waves >= 2 ? 2 : 1);
+        if (w == 4) {
+            const dim3 b4(4 * WAVE);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, true, 4>), grid, b4, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, true, 4>), grid, b4, 0, st, a);
+            return hipGetLastError();
+        }
+        if (w == 2) {
+            const dim3 b2(2 * WAVE);
+            if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, true, 2>), grid, b2, 0, st, a);
+            else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, true, 2>), grid, b2, 0, st, a);
+            else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false, true, 2>), grid, b2, 0, st, a);
+            return hipGetLastError();
+        }
+    }
     if (a.k <= 64) hipLaunchKernelGGL((row_kernel<ET, KT, 64, false, false, true>), grid, block, 0, st, a);
     else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<ET, KT, 128, false, false, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((row_kernel<ET, KT, 256, false, false, true>), grid, block, 0, st, a);
@@ -878,10 +894,10 @@ hipError_t launch_rows_stored(const RowArgs &a, int dtype, hipStream_t st)
     if (a.T <= 0) return hipSuccess;
     if (dtype == JP_BF16) {
         const int64_t nchunks = (a.V + Bf16Elem::VEC - 1) / Bf16Elem::VEC;
-        if (nchunks <= 65535) return launch_rows_stored_k<Bf16Elem, Key32>(a, st);
-        return launch_rows_stored_k<Bf16Elem, Key64>(a, st);
+        if (nchunks <= 65535) return launch_rows_stored_k<Bf16Elem, Key32, true>(a, st);
+        return launch_rows_stored_k<Bf16Elem, Key64, false>(a, st);
     }
-    return launch_rows_stored_k<F32Elem, Key64>(a, st);
+    return launch_rows_stored_k<F32Elem, Key64, true>(a, st);
 }
 
 }  // namespace jp

@@ -157,3 +157,23 @@ def test_vocabulary_of_the_named_workloads(dtype, T):
     rows = np.unique(np.linspace(0, T - 1, 24).astype(np.int64))
     R = pu.run_oracle(w, rows=rows)
     pu.check_rows(buf, w, R, rows=rows, flags=FLAGS)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_case_split_stored_actor_side(seed):
+    """The stored-actor form splits its rows by the same rule: against the oracle in both forms, and
+    the two forms against each other."""
+    import test_gpu_stored as stored_form
+    c = _case(100 + seed)
+    rule = seed % 3
+    _say({n: (str(v) if n == "dtype" else v) for n, v in c.items()} | {"rule": rule})
+    w = _workload(c, 100 + seed)
+    stored = stored_form.stored_side(w, w.k)
+    buf, R, st = stored_form.run_case(w, rule, 2, *stored)
+    ref, R1, st1 = stored_form.run_case(w, rule, 2 | ONE, *stored)
+    tol = pu.TOL[w.actor.dtype]
+    for name in ("topk_policy", "union_size"):
+        assert np.array_equal(getattr(buf, name).cpu().numpy(), getattr(ref, name).cpu().numpy()), name
+    for name in ("accept_prob", "z_approx"):
+        np.testing.assert_allclose(getattr(buf, name).cpu().numpy(), getattr(ref, name).cpu().numpy(), rtol=tol,
+                                   atol=1e-30, equal_nan=True, err_msg=name)
