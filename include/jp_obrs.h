@@ -213,9 +213,9 @@ jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *r
  *   H_policy [T, d_policy], W_policy [d_policy, V] (or [V, d_policy]) likewise
  *   vocab_chunk: columns per chunk (rounded up to a multiple of 256); 0 = default (4096)
  * JP_FLAG_EXACT_Z is not available here (JP_ERR_UNSUPPORTED): the logits are gone after one pass.
- * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit buffers [T, 2 chunk]: the row stage
- * runs once per two chunks; the transposed weight chunks, a per-row record of ~1.6 KB at
- * k <= 64, plus the jp_obrs_forward workspace; 1.1 GB at T = 16384 with the default chunk).
+ * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit buffers [T, 4 chunk]: the row stage
+ * runs once per four chunks; the transposed weight chunks, a per-row record of ~1.6 KB at
+ * k <= 64, plus the jp_obrs_forward workspace; 2.2 GB at T = 16384 with the default chunk).
  */
 size_t jp_obrs_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy,
                                       int32_t k, int64_t vocab_chunk);

@@ -185,7 +185,7 @@ jp_status finalize_impl(int64_t T, const int32_t *ids, const float *uni_given, c
 
 // ---- fused lm_head path ------------------------------------------------------------------------
 
-constexpr int64_t LM_GROUP = 2;
+constexpr int64_t LM_GROUP = 4;
 
 struct LmheadPlan {
     int64_t group, ldc;
