@@ -208,6 +208,9 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
     using SK = typename SO::SortKey;
     const int lane = threadIdx.x & (WAVE - 1);
     const int wv = W > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
+    // Split rows with two tensors: after the sweep wave 0 ranks the actor's top-k while wave 1 ranks
+    // the policy's, each with a candidate pool of its own.
+    constexpr bool PAR = W > 1 && !STORED;
 
     // One LDS pool, used twice: during the sweep it holds the two descriptor buffers; once the
     // surviving descriptors sit in registers it holds the element candidates of the expansion.
@@ -220,21 +223,24 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
     __shared__ __attribute__((aligned(16))) unsigned char pool[POOL_BYTES];
     // split rows: descriptor buffers of waves 1 .. W-1, and what every wave hands to wave 0
     static_assert(W == 1 || W * KC <= C, "C / W descriptors per wave must hold the k best");
-    __shared__ Key s_more[W > 1 ? (W - 1) * 2 * C : 1];
+    __shared__ __attribute__((aligned(16))) Key s_more[W > 1 ? (W - 1) * 2 * C : 1];
+    static_assert(!PAR || CAND_BYTES <= DESC_BYTES, "wave 1 reuses its descriptor buffers as its candidate pool");
     __shared__ double s_part[W > 1 ? W : 1][3];                     // sums of actor / policy, distillation sum
     __shared__ float s_pref[W > 1 ? W : 1][2];                      // their exponent references
     __shared__ int s_pcnt[W > 1 ? W : 1][2];                        // descriptors kept
     Key *const s_desc0 = (W > 1 && wv > 0) ? s_more + (size_t)(wv - 1) * 2 * C : (Key *)pool;
     Key *const s_desc1 = s_desc0 + C;
-    SK *const s_key = (SK *)pool;                                   // candidate sort keys
-    uint32_t *const s_cid = (uint32_t *)(pool + E * sizeof(SK));    // candidate token ids
+    unsigned char *const cpool = (PAR && wv == 1) ? (unsigned char *)s_more : pool;   // this wave's candidate pool
+    SK *const s_key = (SK *)cpool;                                  // candidate sort keys
+    uint32_t *const s_cid = (uint32_t *)(cpool + E * sizeof(SK));   // candidate token ids
     uint32_t *const s_oth = s_cid + E;                              // the other tensor's logit
     // The two ranked lists (ids, own logits, the other tensor's logits).  List 1 is only written
-    // when the candidates of tensor 1 are no longer needed and takes their place in the pool.
+    // when the candidates of tensor 1 are no longer needed and takes their place in the pool (of
+    // the wave that ranked it: wave 0 copies it from wave 1's pool before the union).
     __shared__ uint32_t list0[3 * KC];
-    uint32_t *const l_id[2] = {list0, (uint32_t *)pool};
-    float *const l_a[2] = {(float *)(list0 + KC), (float *)pool + KC};
-    float *const l_b[2] = {(float *)(list0 + 2 * KC), (float *)pool + 2 * KC};
+    uint32_t *const l_id[2] = {list0, (uint32_t *)cpool};
+    float *const l_a[2] = {(float *)(list0 + KC), (float *)cpool + KC};
+    float *const l_b[2] = {(float *)(list0 + 2 * KC), (float *)cpool + 2 * KC};
 
     const int64_t t = blockIdx.x;
     const int k = A.k;
@@ -387,7 +393,8 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
     double Sq = wave_sum((double)sq.hi + (double)sq.s), Sp = wave_sum((double)sp.hi + (double)sp.s);
     double Dp = DISTILL ? wave_sum((double)sp.dhi + (double)sp.d) : 0.0;
     if constexpr (W > 1) {
-        // ---- split rows: every wave hands its sums and its best descriptors to wave 0 ------------
+        // ---- split rows: every wave hands its sums to wave 0 and its best descriptors to the wave
+        // that ranks the tensor (wave 0; wave 1 for the policy when both tensors are swept) ----------
         constexpr int LIM = C / W;                // >= KC >= k: the k best chunks of a run survive
         Key unused;
         const int n0 = uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, LIM, unused));
@@ -398,28 +405,43 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
             s_pcnt[wv][0] = n0; s_pcnt[wv][1] = n1;
         }
         __syncthreads();
-        if (wv > 0) return;
-        int c0 = n0, c1 = n1;
-        float Mq = sq.M2, Mp = sp.M2;
+        if (!PAR && wv > 0) return;
+        // The lists of the waves are concatenated in wave (= chunk) order behind wave 0's own, which
+        // already sit at the front of the pool's two buffers.
+        Key *const m0 = (Key *)pool, *const m1 = m0 + C;
+        if (wv == 0) {
+            int c0 = n0;
+            float Mq = sq.M2, Mp = sp.M2;
 #pragma unroll
-        for (int w = 1; w < W; ++w) {
-            const Key *src0 = s_more + (size_t)(w - 1) * 2 * C, *src1 = src0 + C;
-            const int a0 = s_pcnt[w][0], a1 = s_pcnt[w][1];
-            for (int e = lane; e < a0; e += WAVE) s_desc0[c0 + e] = src0[e];
-            for (int e = lane; e < a1; e += WAVE) s_desc1[c1 + e] = src1[e];
-            c0 += a0; c1 += a1;
-            Mq = fmaxf(Mq, s_pref[w][0]); Mp = fmaxf(Mp, s_pref[w][1]);
-        }
-        sq.cnt = c0; sp.cnt = c1;
-        // sums on the common (largest) exponent reference, as the lanes of one wave have them
-        Sq = 0.0; Sp = 0.0; Dp = 0.0;
+            for (int w = 1; w < W; ++w) {
+                const Key *src0 = s_more + (size_t)(w - 1) * 2 * C;
+                const int a0 = s_pcnt[w][0];
+                for (int e = lane; e < a0; e += WAVE) m0[c0 + e] = src0[e];
+                c0 += a0;
+                Mq = fmaxf(Mq, s_pref[w][0]); Mp = fmaxf(Mp, s_pref[w][1]);
+            }
+            sq.cnt = c0;
+            // sums on the common (largest) exponent reference, as the lanes of one wave have them
+            Sq = 0.0; Sp = 0.0; Dp = 0.0;
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            const double fq2 = (double)__builtin_amdgcn_exp2f(s_pref[w][0] - Mq);
-            const double fp2 = (double)__builtin_amdgcn_exp2f(s_pref[w][1] - Mp);
-            Sq += s_part[w][0] * fq2; Sp += s_part[w][1] * fp2; Dp += s_part[w][2] * fp2;
+            for (int w = 0; w < W; ++w) {
+                const double fq2 = (double)__builtin_amdgcn_exp2f(s_pref[w][0] - Mq);
+                const double fp2 = (double)__builtin_amdgcn_exp2f(s_pref[w][1] - Mp);
+                Sq += s_part[w][0] * fq2; Sp += s_part[w][1] * fp2; Dp += s_part[w][2] * fp2;
+            }
+            sq.M2 = Mq; sp.M2 = Mp;
         }
-        sq.M2 = Mq; sp.M2 = Mp;
+        if (wv == (PAR ? 1 : 0)) {
+            int c1 = s_pcnt[0][1];
+#pragma unroll
+            for (int w = 1; w < W; ++w) {
+                const Key *src1 = s_more + (size_t)(w - 1) * 2 * C + C;
+                const int a1 = s_pcnt[w][1];
+                for (int e = lane; e < a1; e += WAVE) m1[c1 + e] = src1[e];
+                c1 += a1;
+            }
+            sp.cnt = c1;
+        }
         lds_sync();
     }
 
@@ -447,16 +469,23 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
     // The value bits of the k-th largest chunk maximum are enough: every chunk at or above that
     // value is expanded and the element ranking below is exact.  Only a large plateau of equal
     // maxima makes the select run to the last bit (leaving exactly k chunks).
-    nc[0] = STORED ? 0 : uniform_i(select_top_keys<KT, NS>(s_desc0, sq.cnt, k, false, 2 * KC, kth[0]));
-    nc[1] = uniform_i(select_top_keys<KT, NS>(s_desc1, sp.cnt, k, false, 2 * KC, kth[1]));
+    const bool on0 = !PAR || wv == 0, on1 = !PAR || wv == 1;        // which tensor this wave ranks
+    Key *const d0 = (Key *)pool, *const d1 = d0 + C;                // the (merged) descriptor lists
+    nc[0] = 0; nc[1] = 0;
+    kth[0] = 0; kth[1] = 0;
+    if (!STORED && on0) nc[0] = uniform_i(select_top_keys<KT, NS>(d0, sq.cnt, k, false, 2 * KC, kth[0]));
+    if (on1) nc[1] = uniform_i(select_top_keys<KT, NS>(d1, sp.cnt, k, false, 2 * KC, kth[1]));
     Key dk[2][DS];                                                  // at most 2*KC survive per tensor
 #pragma unroll
     for (int sl = 0; sl < DS; ++sl) {
         const int e = sl * WAVE + lane;
-        dk[0][sl] = (!STORED && e < nc[0]) ? s_desc0[e] : (Key)0;
-        dk[1][sl] = e < nc[1] ? s_desc1[e] : (Key)0;
+        dk[0][sl] = (!STORED && e < nc[0]) ? d0[e] : (Key)0;
+        dk[1][sl] = e < nc[1] ? d1[e] : (Key)0;
     }
-    lds_sync();                                                     // the pool now belongs to the candidates
+    // the pools now belong to the candidates (split rows: wave 1's own buffers, which wave 0 has
+    // finished reading, and the pool, whose policy descriptors wave 1 holds in registers)
+    if constexpr (PAR) __syncthreads();
+    else lds_sync();
 
     int nl[2];
     auto expand = [&](auto tensor_c) {
@@ -626,9 +655,24 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
         }
         lds_sync();
     };
-    if constexpr (STORED) nl[0] = 0;
-    else expand(std::integral_constant<int, 0>{});
-    expand(std::integral_constant<int, 1>{});
+    nl[0] = 0; nl[1] = 0;
+    if constexpr (!STORED) {
+        if (on0) expand(std::integral_constant<int, 0>{});
+    }
+    if (on1) expand(std::integral_constant<int, 1>{});
+    if constexpr (PAR) {
+        if (wv == 1 && lane == 0) s_pcnt[1][1] = nl[1];
+        __syncthreads();
+        if (wv > 0) return;
+        nl[1] = s_pcnt[1][1];
+        const uint32_t *const theirs = (const uint32_t *)s_more;    // list 1 as wave 1 left it
+        for (int r = lane; r < nl[1]; r += WAVE) {
+            l_id[1][r] = theirs[r];
+            l_a[1][r] = __uint_as_float(theirs[KC + r]);
+            l_b[1][r] = __uint_as_float(theirs[2 * KC + r]);
+        }
+        lds_sync();
+    }
 
     // Chunked stored form: the target logit of a stored id is picked up by the launch whose chunk
     // holds it and kept in the row record (in list 0's id slots, which this form never uses).
