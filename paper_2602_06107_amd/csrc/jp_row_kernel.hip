@@ -191,9 +191,12 @@ __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, boo
 // W > 1 gives a row to W wavefronts of one workgroup (for batches too small to fill the chip with
 // one wave per row, where a single wave's instruction stream, not the memory system, sets the
 // time of a row): wave w sweeps the w-th of W contiguous runs of chunks with descriptor buffers of
-// its own and keeps its best C / W descriptors per tensor; then the sums and the surviving
-// descriptors of all waves are put together in wave 0 (in wave order, which is chunk order, so
-// ties still resolve towards the smaller id), and wave 0 alone runs the rest exactly as for W = 1.
+// its own and keeps its best C / W descriptors per tensor; then the sums of all waves go to wave 0
+// and the surviving descriptors are put together in wave order (which is chunk order, so ties
+// still resolve towards the smaller id).  With two tensors wave 0 ranks the actor's top-k while
+// wave 1 ranks the policy's in a candidate pool of its own and hands the list over through LDS;
+// wave 0 alone runs the union and the outputs exactly as for W = 1.  In the stored-actor form
+// wave 0 does all of it.
 template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false, int W = 1>
 __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
