@@ -241,6 +241,31 @@ def test_kl_contraction_and_monotonicity():
         assert z == pytest.approx(1.0, rel=1e-12)
 
 
+# ---- Sec. 3.2 (numerical simulation): Dirichlet pairs at growing distance ----------------------
+# The paper's own noise model is not printed, so nothing numeric is taken from its figure; what the
+# mathematics fixes on such pairs is: at lambda = 1 the normaliser (= acceptance rate) is one minus
+# the total variation distance, hence at least 1 - sqrt(KL(p || q) / 2) (Pinsker), and the
+# post-rejection distribution is never farther from p than q was.
+
+@pytest.mark.parametrize("noise", [0.05, 0.3, 1.0, 2.5])
+def test_dirichlet_pairs_acceptance_is_one_minus_total_variation(noise):
+    rng = np.random.default_rng(int(noise * 100) + 5)
+    V = 500
+    for _ in range(6):
+        q = rng.dirichlet(np.full(V, 0.3)) + 1e-300
+        lq = np.log(q)
+        lp = lq + rng.normal(0.0, noise, V)
+        p = _softmax64(lp)
+        q = _softmax64(lq)
+        out, _, _ = orc.row(lq, lp, 0, 0.5, 1.0, 16)
+        tv = 0.5 * np.abs(p - q).sum()
+        assert out.z_exact == pytest.approx(1.0 - tv, rel=1e-12)
+        assert out.z_exact >= 1.0 - math.sqrt(_kl(p, q) / 2.0) - 1e-12
+        assert out.kl_p_qtilde <= out.kl_p_q + 1e-12
+        qt, z = orc.post_rejection(lq, lp, 1.0)
+        np.testing.assert_allclose(qt, np.minimum(q, p) / (1.0 - tv), rtol=1e-12)
+
+
 # ---- P8: w = p / q~ -------------------------------------------------------------------------
 
 def test_weight_is_ratio_to_post_rejection_distribution():
