@@ -255,3 +255,24 @@ def test_long_fp32_rows_of_equal_logits(flags):
     got = obrs.jp_obrs_token_logprob(w.policy, x).cpu().numpy().astype(np.float64)
     want = orc.token_logprob(wl.logits_to_numpy(w.policy), x.cpu().numpy())
     assert np.abs(got - want).max() <= 3.3e-6
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("noise", [0.3, 2.5])
+def test_dirichlet_rows_of_wide_dynamic_range(dtype, noise):
+    """Logits that are the log-probabilities of sparse Dirichlet draws (the simulation of Sec. 3.2):
+    a few tokens carry the mass, most sit hundreds of units below, some are exactly -inf."""
+    T, V, k = 12, 20000, 40
+    _say(f"{dtype} T={T} V={V} k={k} Dirichlet(0.05) log-probabilities, noise {noise}")
+    rng = np.random.default_rng(77 + int(noise * 10))
+    q = rng.dirichlet(np.full(V, 0.05), size=T)
+    with np.errstate(divide="ignore"):
+        lq = np.log(q)                                                       # -inf where the draw underflowed
+    lp = lq + rng.normal(0.0, noise, (T, V))
+    x = np.array([rng.choice(V, p=row) for row in q], dtype=np.int32)
+    a = torch.tensor(lq, dtype=torch.float32, device=DEV).to(dtype)
+    p = torch.tensor(lp, dtype=torch.float32, device=DEV).to(dtype)
+    w = wl.Workload("dirichlet", a, p, torch.tensor(x, device=DEV),
+                    torch.tensor(rng.random(T), dtype=torch.float32, device=DEV), lam=1.0, k=k)
+    buf, R, st = pu.check_all(w, ALL_FLAGS)
+    assert int(st.n_valid) == T
