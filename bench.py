@@ -145,8 +145,8 @@ def bench_lm_head(args, torch, obrs, wl, dev):
         "value": T * args.steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
-        "config": {"workload": "lm_head: T=%d, d_actor=%d, d_policy=%d, V=%d, k=%d, lambda=%g, chunk=%d, W as %s"
-                               % (T, da, dp, V, w.k, w.lam, args.vocab_chunk or 4096,
+        "config": {"workload": "lm_head: T=%d, d_actor=%d, d_policy=%d, V=%d, k=%d, lambda=%g, chunk=%s, W as %s"
+                               % (T, da, dp, V, w.k, w.lam, args.vocab_chunk or "library default (4096 at this T)" if T > 6144 or args.vocab_chunk else "library default (from T)",
                                   "[V, d]" if args.w_vocab_major else "[d, V]"),
                    "kappa": st.kappa, "alpha_hat": st.alpha_hat},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,

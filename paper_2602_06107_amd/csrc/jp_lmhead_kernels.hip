@@ -312,6 +312,9 @@ hipError_t launch_touch_rows(const void *W, int64_t bytes, void *sink, hipStream
 {
     const int64_t n16 = bytes / 16;
     if (n16 <= 0) return hipSuccess;
+    // a chunk that cannot stay in the Infinity Cache beside its logits (the wide chunks of small
+    // batches) would only be read twice
+    if (bytes > ((int64_t)96 << 20)) return hipSuccess;
     const unsigned blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
     hipLaunchKernelGGL(touch_rows_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4 *)W, n16, (uint32_t *)sink);
     return hipGetLastError();
