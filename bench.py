@@ -100,9 +100,10 @@ def bench_lm_head(args, torch, obrs, wl, dev):
     nbytes = obrs.jp_obrs_lmhead_workspace_bytes(T, V, da, dp, w.k, args.vocab_chunk)
     buf = obrs.alloc_buffers(T, V, w.k, obrs.JP_F32, 0, dev, workspace_bytes=nbytes)
 
-    Wa, Wp, lm_flags = w.W_actor, w.W_policy, 0
+    one_wave = args.flags & obrs.JP_FLAG_ONE_WAVE_PER_ROW          # the only --flags bit this workload takes
+    Wa, Wp, lm_flags = w.W_actor, w.W_policy, one_wave
     if args.w_vocab_major:
-        Wa, Wp, lm_flags = w.W_actor.t().contiguous(), w.W_policy.t().contiguous(), obrs.JP_FLAG_W_VOCAB_MAJOR
+        Wa, Wp, lm_flags = w.W_actor.t().contiguous(), w.W_policy.t().contiguous(), obrs.JP_FLAG_W_VOCAB_MAJOR | one_wave
 
     def step():
         obrs.jp_obrs_forward_lmhead(w.H_actor, Wa, w.H_policy, Wp, w.sampled_ids,

@@ -77,8 +77,8 @@ enum {
                                    of the vocabulary, the layout of an output embedding) instead
                                    of [d, V]; no transpose is then needed                     */
     JP_FLAG_ONE_WAVE_PER_ROW = 32 /* never split a row over several wavefronts (the library does
-                                   so by itself for small batches, T <= 1792, in the two-tensor
-                                   and stored-actor forms; the index lists are the same either way, floats agree
+                                   so by itself for small batches, T <= 1792, in the two-tensor,
+                                   stored-actor and lm_head forms; the index lists are the same either way, floats agree
                                    to rounding of the log-sum-exp; the exact-normaliser sweep
                                    follows the row stage; jp_obrs_token_logprob and
                                    jp_obrs_lambda_for_budget, which take no flags, always

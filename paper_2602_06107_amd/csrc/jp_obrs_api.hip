@@ -322,6 +322,7 @@ jp_status jp_obrs_forward_lmhead_stored(const void *H_policy, int64_t d_policy, 
             const bool last = j + 1 == pl.nchunks;
             if (slot + 1 == pl.group || last) {
                 a.V = group_cols; a.id_base = group_base; a.carry_in = groups_done > 0; a.carry_out = !last;
+                a.waves = (prm->flags & JP_FLAG_ONE_WAVE_PER_ROW) ? 1 : jp::waves_per_row(T, group_cols, 4);
                 if (jp::launch_rows_carry_stored(a, st) != hipSuccess) return JP_ERR_HIP;
                 ++groups_done;
             }
@@ -416,6 +417,7 @@ jp_status jp_obrs_forward_lmhead(const void *H_actor, int64_t d_actor, const voi
             const bool last = j + 1 == pl.nchunks;
             if (slot + 1 == pl.group || last) {               // the group is complete: one row-stage launch over it
                 a.V = group_cols; a.id_base = group_base; a.carry_in = groups_done > 0; a.carry_out = !last;
+                a.waves = (prm->flags & JP_FLAG_ONE_WAVE_PER_ROW) ? 1 : jp::waves_per_row(T, group_cols, 4);
                 if (jp::launch_rows_carry(a, st) != hipSuccess) return JP_ERR_HIP;
                 ++groups_done;
             }

@@ -20,7 +20,7 @@ struct RowArgs {
     float lambda;
     double ln_lambda;                 // log(lambda), taken on the host
     int k;
-    int waves;                        // wavefronts per row (1, 2 or 4; not in the vocabulary-chunked forms)
+    int waves;                        // wavefronts per row (1, 2 or 4)
     // per-row results: never nullptr (user buffer or workspace)
     float *accept, *logq, *logp, *logratio, *zapprox;
     float *kl;                        // KL(p || q) per token (distill != 0 only)

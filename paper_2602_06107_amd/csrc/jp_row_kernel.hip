@@ -196,11 +196,11 @@ __device__ __forceinline__ void raise_reference(Stream<Key> &st, float cmax, boo
 // still resolve towards the smaller id).  With two tensors wave 0 ranks the actor's top-k while
 // wave 1 ranks the policy's in a candidate pool of its own and hands the list over through LDS;
 // wave 0 alone runs the union and the outputs exactly as for W = 1.  In the stored-actor form
-// wave 0 does all of it.
+// wave 0 does all of it.  In the chunked forms the carried sums enter through wave 0, every wave
+// starts from the carried thresholds, and wave 0 writes the record.
 template <class ET, class KT, int KC, bool CARRY, bool DISTILL, bool STORED = false, int W = 1>
 __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ? 7 : 8) : (sizeof(typename KT::Key) > 4 ? 1 : (KC <= 128 ? 6 : 4)))) void row_kernel(RowArgs A)
 {
-    static_assert(W == 1 || !CARRY, "rows are not split in the vocabulary-chunked forms");
     using Key = typename KT::Key;
     constexpr int VEC = ET::VEC;
     constexpr int C = (KC >= 256 ? 3 : 4) * KC;   // descriptor buffer capacity per tensor
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(64 * W, (KC <= 64 ? (sizeof(typename KT::Key) > 4 ?
         // Resume the scan: the carried sums go to lane 0, and a full carried list bounds what can
         // still enter the top-k (its k-th value), exactly as if the sweep had never stopped.
         sq.M2 = hdr->M2[0]; sp.M2 = hdr->M2[1];
-        if (lane == 0) { sq.s = (float)hdr->S[0]; sp.s = (float)hdr->S[1]; sp.d = (float)hdr->D; }
+        if (lane == 0 && wv == 0) { sq.s = (float)hdr->S[0]; sp.s = (float)hdr->S[1]; sp.d = (float)hdr->D; }
         if (sq.M2 != M2_UNSET) sq.mthr = (sq.M2 + RESCALE_MARGIN2) / LOG2E_F;
         if (sp.M2 != M2_UNSET) sp.mthr = (sp.M2 + RESCALE_MARGIN2) / LOG2E_F;
         nl_in[0] = hdr->nl[0]; nl_in[1] = hdr->nl[1];
@@ -873,30 +873,41 @@ static hipError_t launch_rows_k(const RowArgs &a, hipStream_t st)
     return a.distill ? launch_rows_kd<ET, KT, SPLIT, true>(a, st) : launch_rows_kd<ET, KT, SPLIT, false>(a, st);
 }
 
+// The vocabulary-chunked forms (fp32 logit chunks, 64-bit keys): the same split by a.waves.
+template <bool DISTILL, bool STORED>
+static hipError_t launch_rows_carry_ds(const RowArgs &a, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.T), block(WAVE);
+    const int w = a.waves >= 4 && a.k <= 128 ? 4 : (a.waves >= 2 ? 2 : 1);
+    if (w == 4) {
+        const dim3 b4(4 * WAVE);
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, DISTILL, STORED, 4>), grid, b4, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, DISTILL, STORED, 4>), grid, b4, 0, st, a);
+        return hipGetLastError();
+    }
+    if (w == 2) {
+        const dim3 b2(2 * WAVE);
+        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, DISTILL, STORED, 2>), grid, b2, 0, st, a);
+        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, DISTILL, STORED, 2>), grid, b2, 0, st, a);
+        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, DISTILL, STORED, 2>), grid, b2, 0, st, a);
+        return hipGetLastError();
+    }
+    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, DISTILL, STORED>), grid, block, 0, st, a);
+    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, DISTILL, STORED>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, DISTILL, STORED>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_rows_carry(const RowArgs &a, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
-    const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.distill) {
-        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, true>), grid, block, 0, st, a);
-        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, true>), grid, block, 0, st, a);
-    } else {
-        if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, false>), grid, block, 0, st, a);
-        else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, false>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, false>), grid, block, 0, st, a);
-    }
-    return hipGetLastError();
+    return a.distill ? launch_rows_carry_ds<true, false>(a, st) : launch_rows_carry_ds<false, false>(a, st);
 }
 
 hipError_t launch_rows_carry_stored(const RowArgs &a, hipStream_t st)
 {
     if (a.T <= 0) return hipSuccess;
-    const dim3 grid((unsigned)a.T), block(WAVE);
-    if (a.k <= 64) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 64, true, false, true>), grid, block, 0, st, a);
-    else if (a.k <= 128) hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 128, true, false, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_kernel<F32Elem, Key64, 256, true, false, true>), grid, block, 0, st, a);
-    return hipGetLastError();
+    return launch_rows_carry_ds<false, true>(a, st);
 }
 
 hipError_t launch_rows(const RowArgs &a, int dtype, hipStream_t st)

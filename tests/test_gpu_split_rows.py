@@ -177,3 +177,37 @@ def test_random_case_split_stored_actor_side(seed):
     for name in ("accept_prob", "z_approx"):
         np.testing.assert_allclose(getattr(buf, name).cpu().numpy(), getattr(ref, name).cpu().numpy(), rtol=tol,
                                    atol=1e-30, equal_nan=True, err_msg=name)
+
+
+@pytest.mark.parametrize("T,V,da,dp,k,chunk", [
+    (40, 9000, 128, 192, 20, 1024),      # groups of 4096 columns: four waves, then a ragged last group
+    (21, 9000, 64, 128, 200, 512),       # k class 256: two waves
+    (130, 5000, 64, 64, 64, 256),        # groups of 1024 columns: two waves
+    (9, 30000, 64, 64, 128, 0),          # one wide chunk, four waves, no carried record at all
+])
+def test_chunked_forms_split_rows_too(T, V, da, dp, k, chunk):
+    """The vocabulary-chunked forms (logits from the matrix cores, row records carried between
+    launches) split their rows by the same rule: against the oracle, and against the one-wave form of
+    the same call, whose GEMM output is bit-identical, so the index lists must be too."""
+    import test_gpu_lmhead as lm
+    import test_gpu_lmhead_stored as lms
+    _say(f"lm_head T={T} V={V} d=({da},{dp}) k={k} chunk={chunk}")
+    w = wl.lm_head(T, V, da, dp, DEV, seed=300 + T, k=k).with_params(lam=0.8)
+    w.ref_logprob = -torch.rand(T, device=DEV)
+    flags = obrs.JP_FLAG_TOPK_LOGPROBS | obrs.JP_FLAG_DISTILL_KL
+    buf = lm._run(w, flags, chunk)
+    lm._check(w, buf, np.arange(T), flags)
+    ref = lm._run(w, flags | ONE, chunk)
+    for name in ("topk_actor", "topk_policy", "union_size"):
+        assert torch.equal(buf.tensors[name], ref.tensors[name]), name
+    for name in ("accept_prob", "z_approx", "logq", "logp", "distill_kl", "topk_actor_logq", "topk_policy_logp"):
+        np.testing.assert_allclose(buf.tensors[name].cpu().numpy(), ref.tensors[name].cpu().numpy(),
+                                   rtol=1e-5, atol=1e-5, err_msg=name)
+    rows = np.arange(T)
+    got, _ = lms.run_case(w, 1, rows, flags=obrs.JP_FLAG_TOPK_LOGPROBS, vocab_chunk=chunk)
+    one, _ = lms.run_case(w, 1, rows, flags=obrs.JP_FLAG_TOPK_LOGPROBS | ONE, vocab_chunk=chunk)
+    for name in ("topk_policy", "union_size"):
+        assert torch.equal(got.tensors[name], one.tensors[name]), name
+    for name in ("accept_prob", "z_approx", "logp"):
+        np.testing.assert_allclose(got.tensors[name].cpu().numpy(), one.tensors[name].cpu().numpy(),
+                                   rtol=1e-5, atol=1e-5, err_msg=name)
