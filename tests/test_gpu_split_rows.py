@@ -1,7 +1,7 @@
 """Rows split over two or four wavefronts (what the library does by itself for small batches of
-long rows in the two-tensor form) against the oracle and against
-the one-wave-per-row form of the same call (JP_FLAG_ONE_WAVE_PER_ROW): index lists and union sizes
-must be identical, floats agree to the tolerance of the dtype."""
+long rows, in the two-tensor, stored-actor and vocabulary-chunked forms) against the oracle and
+against the one-wave-per-row form of the same call (JP_FLAG_ONE_WAVE_PER_ROW): index lists and
+union sizes must be identical, floats agree to the tolerance of the dtype."""
 import numpy as np
 import pytest
 import torch
