@@ -212,7 +212,7 @@ jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *r
  *            row-major, contiguous, 16-byte aligned
  *   H_policy [T, d_policy], W_policy [d_policy, V] (or [V, d_policy]) likewise
  *   vocab_chunk: columns per chunk (rounded up to a multiple of 256); 0 = chosen from T
- *            (4096 for T > 6144, 8192 down to T = 1537, 16384 down to T = 769, 32768 below)
+ *            (4096 for T > 6144, 8192 down to T = 1537, 16384 down to T = 769, 65536 below)
  * JP_FLAG_EXACT_Z is not available here (JP_ERR_UNSUPPORTED): the logits are gone after one pass.
  * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit buffers [T, 4 chunk]: the row stage
  * runs once per four chunks; the transposed weight chunks, a per-row record of ~1.6 KB at

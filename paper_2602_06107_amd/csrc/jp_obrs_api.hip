@@ -202,8 +202,10 @@ bool plan_lmhead(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy, int32_
     if (d_actor < 0 || d_policy <= 0 || d_actor % 64 || d_policy % 64 || d_actor > (1 << 20) || d_policy > (1 << 20)) return false;
     // Default width: a chunk of 4096 columns keeps the logit buffers of a large batch in the caches
     // between the GEMM and the row stage; a small batch has few row tiles, and needs wider chunks for
-    // its GEMM launches to fill the chip (T = 256: 4.5 ms per call at 4096 columns, 1.7 at 32768).
-    const int64_t by_batch = T <= 768 ? 32768 : (T <= 1536 ? 16384 : (T <= 6144 ? 8192 : 4096));
+    // its GEMM launches to fill the chip, in two generations of workgroups at least, so that the short
+    // tiles of the actor head fill in behind the policy head's (T = 256: 4.5 ms per call at 4096
+    // columns, 1.7 at 65536).
+    const int64_t by_batch = T <= 768 ? 65536 : (T <= 1536 ? 16384 : (T <= 6144 ? 8192 : 4096));
     int64_t c = vocab_chunk > 0 ? vocab_chunk : by_batch;
     c = (c + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
     const int64_t vpad = (V + jp::LMHEAD_N_ALIGN - 1) / jp::LMHEAD_N_ALIGN * jp::LMHEAD_N_ALIGN;
