@@ -216,7 +216,8 @@ jp_status jp_obrs_finalize(int64_t T, const int32_t *sampled_ids, const float *r
  * JP_FLAG_EXACT_Z is not available here (JP_ERR_UNSUPPORTED): the logits are gone after one pass.
  * Workspace: jp_obrs_lmhead_workspace_bytes (two fp32 logit buffers [T, 4 chunk]: the row stage
  * runs once per four chunks; the transposed weight chunks, a per-row record of ~1.6 KB at
- * k <= 64, plus the jp_obrs_forward workspace; 2.2 GB at T = 16384 with the default chunk).
+ * k <= 64, plus the jp_obrs_forward workspace; 2.2 GB at T = 16384 and no more than that at any
+ * smaller T with the default chunk, V = 151936, d = 2048 + 4096).
  */
 size_t jp_obrs_lmhead_workspace_bytes(int64_t T, int64_t V, int64_t d_actor, int64_t d_policy,
                                       int32_t k, int64_t vocab_chunk);
